@@ -1,0 +1,142 @@
+/*
+ * pbkv.h -- C boundary of the MI355X prefix-reuse prefill library (libpbkv.so).
+ *
+ * The operations are the GPU-side work that the paper's cache policy exists to
+ * make cheap (Sec. 1 and Sec. 2 of arxiv 2605.06472, "PBKV"): a request whose
+ * prompt prefix is cached in the radix tree prefills only its uncached suffix
+ * against the cached KV pages; the KV it produces is kept for downstream
+ * agents; pages evicted to the host tier are swapped back on a hit or loaded
+ * ahead of time by the prefetcher (Sec. 4.3).
+ *
+ * Conventions common to all calls
+ *   - Plain pointers and sizes only.  "device" = memory of the current HIP
+ *     device; "host" = ordinary host memory read during the call; "pinned" =
+ *     page-locked host memory (hipHostMalloc, or a pinned torch tensor) that
+ *     the GPU reads while the stream runs.
+ *   - The caller owns every buffer and the stream.  The library keeps no
+ *     caller pointer after the call returns.  It owns a small per-device ring
+ *     of pinned descriptor memory, created on first use and released at
+ *     process exit.
+ *   - `stream` is a hipStream_t passed as void*; NULL is the default stream.
+ *     Calls validate on the host, enqueue on `stream`, and return without
+ *     waiting.  Buffers must stay valid until the stream has run the work.
+ *   - Return value: PBKV_OK or a negative pbkv_status.  On an argument error
+ *     nothing is enqueued.  pbkv_last_error() gives a thread-local message.
+ *   - Layouts are row-major, innermost dimension last:
+ *       q, out        [N][num_q_heads][head_dim]   N = sum(new_lens), requests
+ *                                                  packed in batch order
+ *       k_new, v_new  [N][num_kv_heads][head_dim]
+ *       kv_pool       [num_pages][2][num_kv_heads][page_size][head_dim]
+ *                     (index 0 = K, 1 = V): one page is one contiguous block
+ *                     of pbkv_page_bytes() bytes
+ *       block_table   [batch][max_pages_per_req] int32: physical page of each
+ *                     logical page of the request (prefix pages first, then
+ *                     the pages the suffix is appended to)
+ *   - Supported shapes: page_size 16; head_dim 64 or 128; num_q_heads a
+ *     multiple of num_kv_heads with ratio 1, 2, 4, 8 or 16 for PBKV_BF16 and
+ *     any ratio for PBKV_F32.  Anything else returns PBKV_ERR_SHAPE; there is
+ *     no slow fallback.
+ */
+#ifndef PBKV_H
+#define PBKV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PBKV_OK = 0,
+    PBKV_ERR_NULL = -1,    /* a required pointer is NULL                          */
+    PBKV_ERR_SHAPE = -2,   /* unsupported or inconsistent shape                   */
+    PBKV_ERR_DTYPE = -3,   /* unknown dtype                                       */
+    PBKV_ERR_RANGE = -4,   /* a length or page id does not fit the table / pool   */
+    PBKV_ERR_ALIAS = -5,   /* duplicate destination pages in a swap-in            */
+    PBKV_ERR_DEVICE = -6,  /* HIP runtime error, or a pointer of the wrong kind   */
+    PBKV_ERR_LIMIT = -7    /* the call needs more descriptor space than the library
+                              can provide at once                                 */
+} pbkv_status;
+
+typedef enum { PBKV_BF16 = 0, PBKV_F32 = 1 } pbkv_dtype;
+
+typedef struct {
+    int32_t batch;              /* B: requests in this call (0 is a valid no-op)   */
+    int32_t num_q_heads;        /* H_q                                             */
+    int32_t num_kv_heads;       /* H_kv                                            */
+    int32_t head_dim;           /* d                                               */
+    int32_t page_size;          /* P: tokens per page (16)                         */
+    int32_t num_pages;          /* pages in kv_pool                                */
+    int32_t max_pages_per_req;  /* row length of block_table                       */
+    int32_t dtype;              /* pbkv_dtype of q, k_new, v_new, kv_pool, out     */
+} pbkv_shape;
+
+/* Bytes of one pool page for this shape (2 * H_kv * P * d * element size); 0 if the
+ * shape is unsupported. */
+int64_t pbkv_page_bytes(const pbkv_shape *shape);
+
+/*
+ * Prefix-reuse prefill attention (Sec. 1: a cache hit turns prefill of the shared
+ * context into a lookup; Sec. 2: radix-tree prefix sharing).  For request r with
+ * cached prefix length p = prefix_lens[r] and n = new_lens[r] new tokens, suffix row
+ * i and query head h:
+ *     out = sum_t softmax_t(q . k_t / sqrt(d)) v_t
+ * over t in [0, p) read from kv_pool through block_table[r] with KV head
+ * h / (H_q / H_kv), followed by the request's own suffix tokens 0..i read from
+ * k_new / v_new (causal, diagonal included).  The suffix is NOT read from the pool,
+ * so pbkv_append_kv may run concurrently on another stream.
+ *
+ *   q, k_new, v_new, kv_pool, block_table : device, read only
+ *   prefix_lens, new_lens                 : host int32 [batch], read during the call
+ *   out                                   : device, written; rows of other calls untouched
+ * bf16: fp32 accumulation, probabilities rounded to bf16 before the PV product, one
+ * final rounding to bf16.  f32: fp32 throughout.
+ * Page ids read from block_table are clamped to [0, num_pages) on the device, so a
+ * corrupt table gives wrong numbers, never an out-of-bounds access.
+ * Errors: NULL pointers, unsupported shape, negative lengths, or
+ * ceil((p + n) / P) > max_pages_per_req  ->  negative status, nothing enqueued.
+ */
+int pbkv_prefix_prefill(const pbkv_shape *shape, const void *q, const void *k_new,
+                        const void *v_new, const void *kv_pool, const int32_t *block_table,
+                        const int32_t *prefix_lens, const int32_t *new_lens, void *out,
+                        void *stream);
+
+/*
+ * Paged KV append (Sec. 1: the KV-Cache an agent produces is retained for downstream
+ * agents).  Suffix token t of request r is copied, for K and V and every KV head, to
+ * page block_table[r][(p + t) / P], slot (p + t) % P.  Byte-exact copy; no other pool
+ * byte is written.
+ *   k_new, v_new, block_table : device, read only;  kv_pool : device, written
+ *   prefix_lens, new_lens     : host int32 [batch]
+ * Requests must not share a destination slot (their suffix pages are private).
+ */
+int pbkv_append_kv(const pbkv_shape *shape, const void *k_new, const void *v_new,
+                   void *kv_pool, const int32_t *block_table, const int32_t *prefix_lens,
+                   const int32_t *new_lens, void *stream);
+
+/*
+ * Host -> pool page swap-in (Sec. 2: HiCache keeps evicted cache in host memory and
+ * swaps it back on a hit; Sec. 4.3: the prefetcher loads host nodes into free or
+ * retired GPU space ahead of the hit).  Pool page page_ids[i] := host page i, whole
+ * pages, byte-exact.
+ *   host_pages : pinned host memory, [n_pages][pbkv_page_bytes], read by the GPU while
+ *                the stream runs (must stay valid and unmodified until then)
+ *   page_ids   : host int32 [n_pages], read during the call; each in [0, num_pages),
+ *                all distinct (else PBKV_ERR_RANGE / PBKV_ERR_ALIAS, nothing enqueued)
+ *   kv_pool    : device, written
+ * Only shape->num_kv_heads, head_dim, page_size, num_pages and dtype are used.
+ */
+int pbkv_swap_in_pages(const pbkv_shape *shape, const void *host_pages,
+                       const int32_t *page_ids, int32_t n_pages, void *kv_pool,
+                       void *stream);
+
+/* Thread-local, library-owned description of the last error on this thread ("" if none). */
+const char *pbkv_last_error(void);
+
+/* Library version string, e.g. "pbkv 0.1 gfx950". */
+const char *pbkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PBKV_H */

@@ -1,0 +1,327 @@
+// Host side of libpbkv: argument validation, work-list construction and launches behind
+// the C boundary declared in include/pbkv.h.  No attention, append or swap-in arithmetic
+// happens on the host: the host only cuts the batch into tiles / page runs and enqueues
+// the kernels.
+#include "../../include/pbkv.h"
+#include "pbkv_internal.h"
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <mutex>
+#include <vector>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int fail_hip(hipError_t e, const char *what) {
+    return fail(PBKV_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+int elt_bytes(int dtype) { return dtype == PBKV_BF16 ? 2 : 4; }
+
+// Shape checks that need no device.  `need_heads` = the call uses the query-head count.
+int check_shape(const pbkv_shape *s, bool need_heads) {
+    if (!s) return fail(PBKV_ERR_NULL, "shape is NULL");
+    if (s->dtype != PBKV_BF16 && s->dtype != PBKV_F32) return fail(PBKV_ERR_DTYPE, "unknown dtype %d", s->dtype);
+    if (s->page_size != 16) return fail(PBKV_ERR_SHAPE, "page_size %d unsupported (16)", s->page_size);
+    if (s->head_dim != 64 && s->head_dim != 128)
+        return fail(PBKV_ERR_SHAPE, "head_dim %d unsupported (64, 128)", s->head_dim);
+    if (s->num_kv_heads <= 0) return fail(PBKV_ERR_SHAPE, "num_kv_heads %d", s->num_kv_heads);
+    if (s->num_pages <= 0) return fail(PBKV_ERR_SHAPE, "num_pages %d", s->num_pages);
+    if (need_heads) {
+        if (s->num_q_heads <= 0 || s->num_q_heads % s->num_kv_heads != 0)
+            return fail(PBKV_ERR_SHAPE, "num_q_heads %d is not a multiple of num_kv_heads %d",
+                        s->num_q_heads, s->num_kv_heads);
+        const int G = s->num_q_heads / s->num_kv_heads;
+        if (s->dtype == PBKV_BF16 && !(G == 1 || G == 2 || G == 4 || G == 8 || G == 16))
+            return fail(PBKV_ERR_SHAPE, "query/KV head ratio %d unsupported for bf16 (1,2,4,8,16)", G);
+    }
+    if (s->batch < 0 || s->max_pages_per_req < 0) return fail(PBKV_ERR_SHAPE, "negative batch or table width");
+    return PBKV_OK;
+}
+
+int check_lens(const pbkv_shape *s, const int32_t *prefix_lens, const int32_t *new_lens, int64_t *total) {
+    int64_t N = 0;
+    for (int r = 0; r < s->batch; r++) {
+        const int64_t p = prefix_lens[r], n = new_lens[r];
+        if (p < 0 || n < 0) return fail(PBKV_ERR_RANGE, "request %d: negative length (%lld, %lld)", r, (long long)p, (long long)n);
+        if (p + n > INT32_MAX - 4096) return fail(PBKV_ERR_RANGE, "request %d: sequence too long", r);
+        const int64_t pages = n > 0 ? (p + n + s->page_size - 1) / s->page_size : (p + s->page_size - 1) / s->page_size;
+        if (n > 0 && pages > s->max_pages_per_req)
+            return fail(PBKV_ERR_RANGE, "request %d needs %lld pages, block_table rows hold %d", r,
+                        (long long)pages, s->max_pages_per_req);
+        N += n;
+    }
+    *total = N;
+    return PBKV_OK;
+}
+
+int check_aligned(const void *p, const char *name) {
+    if (((uintptr_t)p & 15) != 0) return fail(PBKV_ERR_SHAPE, "%s is not 16-byte aligned", name);
+    return PBKV_OK;
+}
+
+// The pointer must be something a kernel on the current device may dereference.
+int check_device_ptr(const void *p, const char *name) {
+    hipPointerAttribute_t a;
+    hipError_t e = hipPointerGetAttributes(&a, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(PBKV_ERR_DEVICE, "%s: not a device pointer (%s)", name, hipGetErrorString(e));
+    }
+    if (a.type != hipMemoryTypeDevice && a.type != hipMemoryTypeManaged)
+        return fail(PBKV_ERR_DEVICE, "%s: expected device memory", name);
+    return PBKV_OK;
+}
+
+int check_pinned_ptr(const void *p, const char *name, const void **dev_view) {
+    hipPointerAttribute_t a;
+    hipError_t e = hipPointerGetAttributes(&a, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(PBKV_ERR_DEVICE, "%s: not pinned host memory (%s)", name, hipGetErrorString(e));
+    }
+    if (a.type != hipMemoryTypeHost && a.type != hipMemoryTypeManaged && a.type != hipMemoryTypeDevice)
+        return fail(PBKV_ERR_DEVICE, "%s: expected pinned host memory", name);
+    // pinned memory shares one virtual address between host and device
+    *dev_view = p;
+    return PBKV_OK;
+}
+
+// ---- per-device ring of pinned, device-mapped descriptor memory ---------------------------
+// Work lists are written here by the host and read by the kernels through the mapped
+// pointer; a region is reused only after the event recorded behind its kernel has fired.
+struct Ring {
+    char *host = nullptr;
+    char *dev = nullptr;
+    size_t cap = 0, head = 0;
+    struct Pending { hipEvent_t ev; size_t begin, end; };
+    std::deque<Pending> pending;
+    std::vector<hipEvent_t> spare;
+    std::mutex mu;
+};
+constexpr size_t RING_BYTES = 8u << 20;
+constexpr int MAX_DEVICES = 16;
+Ring g_rings[MAX_DEVICES];
+
+struct Lease { Ring *ring; size_t begin, end; char *host; char *dev; };
+
+int ring_acquire(size_t bytes, Lease *out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(PBKV_ERR_DEVICE, "device index %d unsupported", dev);
+    Ring &r = g_rings[dev];
+    std::lock_guard<std::mutex> lk(r.mu);
+    if (!r.host) {
+        void *h = nullptr, *d = nullptr;
+        e = hipHostMalloc(&h, RING_BYTES, hipHostMallocMapped);
+        if (e != hipSuccess) return fail_hip(e, "hipHostMalloc(descriptor ring)");
+        e = hipHostGetDevicePointer(&d, h, 0);
+        if (e != hipSuccess) return fail_hip(e, "hipHostGetDevicePointer");
+        r.host = (char *)h;
+        r.dev = (char *)d;
+        r.cap = RING_BYTES;
+    }
+    bytes = (bytes + 255) & ~(size_t)255;
+    if (bytes > r.cap / 2) return fail(PBKV_ERR_LIMIT, "work list of %zu bytes exceeds the descriptor ring", bytes);
+    if (r.head + bytes > r.cap) r.head = 0;
+    const size_t b = r.head, en = r.head + bytes;
+    // retire finished regions, wait for unfinished ones that overlap the new region
+    for (auto it = r.pending.begin(); it != r.pending.end();) {
+        const bool overlap = it->begin < en && it->end > b;
+        hipError_t q = overlap ? hipEventSynchronize(it->ev) : hipEventQuery(it->ev);
+        if (q == hipSuccess) {
+            r.spare.push_back(it->ev);
+            it = r.pending.erase(it);
+        } else if (q == hipErrorNotReady) {
+            ++it;
+        } else {
+            return fail_hip(q, "descriptor ring event");
+        }
+    }
+    r.head = en;
+    *out = Lease{&r, b, en, r.host + b, r.dev + b};
+    return PBKV_OK;
+}
+
+// Record "the kernels reading this lease are enqueued" on the stream.
+int ring_release(const Lease &l, hipStream_t s) {
+    Ring &r = *l.ring;
+    std::lock_guard<std::mutex> lk(r.mu);
+    hipEvent_t ev;
+    if (!r.spare.empty()) {
+        ev = r.spare.back();
+        r.spare.pop_back();
+    } else {
+        hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+        if (e != hipSuccess) return fail_hip(e, "hipEventCreate");
+    }
+    hipError_t e = hipEventRecord(ev, s);
+    if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
+    r.pending.push_back({ev, l.begin, l.end});
+    return PBKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *pbkv_last_error(void) { return g_err; }
+
+const char *pbkv_version(void) { return "pbkv 0.1 gfx950"; }
+
+int64_t pbkv_page_bytes(const pbkv_shape *s) {
+    if (!s || check_shape(s, false) != PBKV_OK) return 0;
+    return (int64_t)2 * s->num_kv_heads * s->page_size * s->head_dim * elt_bytes(s->dtype);
+}
+
+int pbkv_prefix_prefill(const pbkv_shape *s, const void *q, const void *k_new, const void *v_new,
+                        const void *kv_pool, const int32_t *block_table, const int32_t *prefix_lens,
+                        const int32_t *new_lens, void *out, void *stream) {
+    g_err[0] = 0;
+    int rc = check_shape(s, true);
+    if (rc) return rc;
+    if (s->batch == 0) return PBKV_OK;
+    if (!q || !k_new || !v_new || !kv_pool || !block_table || !prefix_lens || !new_lens || !out)
+        return fail(PBKV_ERR_NULL, "pbkv_prefix_prefill: NULL argument");
+    int64_t N = 0;
+    if ((rc = check_lens(s, prefix_lens, new_lens, &N))) return rc;
+    if (N == 0) return PBKV_OK;
+    if ((rc = check_aligned(q, "q")) || (rc = check_aligned(k_new, "k_new")) || (rc = check_aligned(v_new, "v_new")) ||
+        (rc = check_aligned(kv_pool, "kv_pool")) || (rc = check_aligned(out, "out")))
+        return rc;
+    if ((rc = check_device_ptr(q, "q")) || (rc = check_device_ptr(k_new, "k_new")) ||
+        (rc = check_device_ptr(v_new, "v_new")) || (rc = check_device_ptr(kv_pool, "kv_pool")) ||
+        (rc = check_device_ptr(block_table, "block_table")) || (rc = check_device_ptr(out, "out")))
+        return rc;
+
+    const int G = s->num_q_heads / s->num_kv_heads;
+    const int T = s->dtype == PBKV_BF16 ? pbkv::attn_bf16_tile_tokens(s->head_dim, G) : pbkv::attn_f32_tile_tokens();
+    std::vector<pbkv::TileDesc> tiles;
+    int64_t row0 = 0;
+    for (int r = 0; r < s->batch; r++) {
+        for (int t0 = 0; t0 < new_lens[r]; t0 += T)
+            tiles.push_back(pbkv::TileDesc{r, t0, prefix_lens[r], new_lens[r], row0, 0});
+        row0 += new_lens[r];
+    }
+    // longest tiles first: work per tile grows with the number of visible keys
+    std::stable_sort(tiles.begin(), tiles.end(), [T](const pbkv::TileDesc &a, const pbkv::TileDesc &b) {
+        const int64_t ka = (int64_t)a.prefix_len + std::min(a.tok0 + T, a.new_len);
+        const int64_t kb = (int64_t)b.prefix_len + std::min(b.tok0 + T, b.new_len);
+        return ka > kb;
+    });
+    if (tiles.size() > (size_t)INT32_MAX / 64) return fail(PBKV_ERR_LIMIT, "too many tiles");
+
+    Lease lease;
+    if ((rc = ring_acquire(tiles.size() * sizeof(pbkv::TileDesc), &lease))) return rc;
+    memcpy(lease.host, tiles.data(), tiles.size() * sizeof(pbkv::TileDesc));
+
+    pbkv::AttnParams p;
+    p.q = q; p.k_new = k_new; p.v_new = v_new; p.kv_pool = kv_pool; p.out = out;
+    p.block_table = block_table;
+    p.tiles = (const pbkv::TileDesc *)lease.dev;
+    p.n_tiles = (int32_t)tiles.size();
+    p.Hq = s->num_q_heads; p.Hkv = s->num_kv_heads;
+    p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = s->dtype == PBKV_BF16 ? pbkv::launch_attn_bf16(p, s->head_dim, st)
+                                         : pbkv::launch_attn_f32(p, s->head_dim, st);
+    int rel = ring_release(lease, st);
+    if (e != hipSuccess) return fail_hip(e, "attention launch");
+    return rel;
+}
+
+int pbkv_append_kv(const pbkv_shape *s, const void *k_new, const void *v_new, void *kv_pool,
+                   const int32_t *block_table, const int32_t *prefix_lens, const int32_t *new_lens,
+                   void *stream) {
+    g_err[0] = 0;
+    int rc = check_shape(s, false);
+    if (rc) return rc;
+    if (s->batch == 0) return PBKV_OK;
+    if (!k_new || !v_new || !kv_pool || !block_table || !prefix_lens || !new_lens)
+        return fail(PBKV_ERR_NULL, "pbkv_append_kv: NULL argument");
+    int64_t N = 0;
+    if ((rc = check_lens(s, prefix_lens, new_lens, &N))) return rc;
+    if (N == 0) return PBKV_OK;
+    if ((rc = check_aligned(k_new, "k_new")) || (rc = check_aligned(v_new, "v_new")) ||
+        (rc = check_aligned(kv_pool, "kv_pool")))
+        return rc;
+    if ((rc = check_device_ptr(k_new, "k_new")) || (rc = check_device_ptr(v_new, "v_new")) ||
+        (rc = check_device_ptr(kv_pool, "kv_pool")) || (rc = check_device_ptr(block_table, "block_table")))
+        return rc;
+
+    const int P = s->page_size;
+    std::vector<pbkv::AppendDesc> descs;
+    int64_t row0 = 0;
+    for (int r = 0; r < s->batch; r++) {
+        const int64_t p = prefix_lens[r], n = new_lens[r];
+        for (int64_t t = 0; t < n;) {
+            const int64_t pos = p + t;
+            const int slot0 = (int)(pos % P);
+            const int count = (int)std::min<int64_t>(P - slot0, n - t);
+            descs.push_back(pbkv::AppendDesc{row0 + t, r, (int32_t)(pos / P), slot0, count, 0});
+            t += count;
+        }
+        row0 += n;
+    }
+    Lease lease;
+    if ((rc = ring_acquire(descs.size() * sizeof(pbkv::AppendDesc), &lease))) return rc;
+    memcpy(lease.host, descs.data(), descs.size() * sizeof(pbkv::AppendDesc));
+    pbkv::AppendParams p;
+    p.k_new = k_new; p.v_new = v_new; p.kv_pool = kv_pool; p.block_table = block_table;
+    p.descs = (const pbkv::AppendDesc *)lease.dev;
+    p.n_descs = (int32_t)descs.size();
+    p.Hkv = s->num_kv_heads; p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = pbkv::launch_append(p, s->head_dim, elt_bytes(s->dtype), st);
+    int rel = ring_release(lease, st);
+    if (e != hipSuccess) return fail_hip(e, "append launch");
+    return rel;
+}
+
+int pbkv_swap_in_pages(const pbkv_shape *s, const void *host_pages, const int32_t *page_ids,
+                       int32_t n_pages, void *kv_pool, void *stream) {
+    g_err[0] = 0;
+    int rc = check_shape(s, false);
+    if (rc) return rc;
+    if (n_pages < 0) return fail(PBKV_ERR_RANGE, "n_pages %d", n_pages);
+    if (n_pages == 0) return PBKV_OK;
+    if (!host_pages || !page_ids || !kv_pool) return fail(PBKV_ERR_NULL, "pbkv_swap_in_pages: NULL argument");
+    std::vector<uint8_t> seen((size_t)s->num_pages, 0);
+    for (int i = 0; i < n_pages; i++) {
+        const int32_t id = page_ids[i];
+        if (id < 0 || id >= s->num_pages)
+            return fail(PBKV_ERR_RANGE, "page_ids[%d] = %d outside pool of %d pages", i, id, s->num_pages);
+        if (seen[id]) return fail(PBKV_ERR_ALIAS, "page_ids[%d] = %d appears twice", i, id);
+        seen[id] = 1;
+    }
+    if ((rc = check_aligned(host_pages, "host_pages")) || (rc = check_aligned(kv_pool, "kv_pool"))) return rc;
+    const void *host_dev = nullptr;
+    if ((rc = check_pinned_ptr(host_pages, "host_pages", &host_dev))) return rc;
+    if ((rc = check_device_ptr(kv_pool, "kv_pool"))) return rc;
+
+    Lease lease;
+    if ((rc = ring_acquire((size_t)n_pages * sizeof(int32_t), &lease))) return rc;
+    memcpy(lease.host, page_ids, (size_t)n_pages * sizeof(int32_t));
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = pbkv::launch_swap_in(host_dev, (const int32_t *)lease.dev, n_pages, kv_pool,
+                                        pbkv_page_bytes(s), st);
+    int rel = ring_release(lease, st);
+    if (e != hipSuccess) return fail_hip(e, "swap-in launch");
+    return rel;
+}
+
+}  // extern "C"

@@ -1,0 +1,59 @@
+// Internal declarations shared by the host API and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pbkv {
+
+// One unit of attention work: a block of consecutive suffix tokens of one request.
+// Written by the host into pinned memory and read by the kernel through the mapped
+// pointer (32 bytes, two 16-byte loads).
+struct TileDesc {
+    int32_t req;         // request index inside this call (row of block_table)
+    int32_t tok0;        // first suffix token of the tile
+    int32_t prefix_len;  // p_r
+    int32_t new_len;     // n_r
+    int64_t row0;        // packed row (into q / k_new / v_new / out) of the request's token 0
+    int64_t pad;
+};
+static_assert(sizeof(TileDesc) == 32, "TileDesc is read as two 16-byte words");
+
+// A run of consecutive suffix tokens of one request that land in one pool page.
+struct AppendDesc {
+    int64_t src_row;     // packed row of the first token of the run
+    int32_t req;         // request index (row of block_table)
+    int32_t logical_page;
+    int32_t slot0;       // first slot inside the page
+    int32_t count;       // tokens in the run (1..page_size)
+    int64_t pad;
+};
+static_assert(sizeof(AppendDesc) == 32, "AppendDesc is read as two 16-byte words");
+
+struct AttnParams {
+    const void *q, *k_new, *v_new, *kv_pool;
+    void *out;
+    const int32_t *block_table;
+    const TileDesc *tiles;
+    int32_t n_tiles, Hq, Hkv, max_pages, num_pages;
+};
+
+struct AppendParams {
+    const void *k_new, *v_new;
+    void *kv_pool;
+    const int32_t *block_table;
+    const AppendDesc *descs;
+    int32_t n_descs, Hkv, max_pages, num_pages;
+};
+
+// Tokens per attention tile for a shape (what the host cuts the suffix into).
+int attn_bf16_tile_tokens(int head_dim, int group);
+int attn_f32_tile_tokens();
+
+// Launchers: all arguments already validated.  Return the hipError of the launch.
+hipError_t launch_attn_bf16(const AttnParams &p, int head_dim, hipStream_t s);
+hipError_t launch_attn_f32(const AttnParams &p, int head_dim, hipStream_t s);
+hipError_t launch_append(const AppendParams &p, int head_dim, int elt_bytes, hipStream_t s);
+hipError_t launch_swap_in(const void *host_pages, const int32_t *page_ids_dev, int32_t n_pages,
+                          void *kv_pool, int64_t page_bytes, hipStream_t s);
+
+}  // namespace pbkv

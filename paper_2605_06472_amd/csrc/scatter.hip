@@ -1,0 +1,83 @@
+// Page-granular byte movers: paged KV append and host->pool page swap-in.
+// Both are pure copies (bit-exact) bound by memory bandwidth: HBM for the append,
+// the host link for the swap-in.  Every access is a 16-byte vector access and every
+// (token, K|V, head) row or page is a run of whole 128-byte lines on both sides.
+#include "pbkv_internal.h"
+
+namespace pbkv {
+
+static __device__ __forceinline__ int clamp_page(int pg, int num_pages) {
+    return pg < 0 ? 0 : (pg >= num_pages ? num_pages - 1 : pg);
+}
+
+// One work-group per AppendDesc: up to 16 consecutive suffix tokens of one request that
+// fall in one pool page.  Chunk index order = source order (token, K|V, head, 16B chunk),
+// so a wave reads contiguous memory and writes whole rows of row_bytes.
+__global__ __launch_bounds__(256) void append_kernel(AppendParams p, int row_chunks, int page_size) {
+    const AppendDesc d = p.descs[blockIdx.x];
+    const int pg = clamp_page(p.block_table[(int64_t)d.req * p.max_pages + d.logical_page], p.num_pages);
+    const int per_tok = 2 * p.Hkv * row_chunks;               // 16-byte chunks per token (K and V)
+    const int total = d.count * per_tok;
+    const int64_t page_chunks = (int64_t)per_tok * page_size;
+    const uint4 *ksrc = (const uint4 *)p.k_new;
+    const uint4 *vsrc = (const uint4 *)p.v_new;
+    uint4 *pool = (uint4 *)p.kv_pool + (int64_t)pg * page_chunks;
+    for (int idx = threadIdx.x; idx < total; idx += 256) {
+        const int c = idx % row_chunks;
+        const int g = (idx / row_chunks) % p.Hkv;
+        const int kv = (idx / (row_chunks * p.Hkv)) & 1;
+        const int t = idx / per_tok;
+        const int64_t s = ((d.src_row + t) * p.Hkv + g) * row_chunks + c;
+        const uint4 v = kv ? vsrc[s] : ksrc[s];
+        pool[((int64_t)(kv * p.Hkv + g) * page_size + d.slot0 + t) * row_chunks + c] = v;
+    }
+}
+
+hipError_t launch_append(const AppendParams &p, int head_dim, int elt_bytes, hipStream_t s) {
+    if (p.n_descs == 0) return hipSuccess;
+    const int row_chunks = head_dim * elt_bytes / 16;
+    hipLaunchKernelGGL(append_kernel, dim3(p.n_descs), dim3(256), 0, s, p, row_chunks, 16);
+    return hipGetLastError();
+}
+
+// Swap-in: each work-group moves SWAP_CHUNKS 16-byte chunks of one page from pinned host
+// memory (read over the host link through the mapped pointer) into the page's pool slot.
+// Four independent loads per thread are in flight before the first store.
+constexpr int SWAP_CHUNKS = 1024;   // 16 KiB per work-group
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+__global__ __launch_bounds__(256) void swap_in_kernel(const u32x4 *__restrict__ host_pages,
+                                                      const int32_t *__restrict__ page_ids,
+                                                      u32x4 *__restrict__ pool, int page_chunks,
+                                                      int wgs_per_page) {
+    const int page = blockIdx.x / wgs_per_page;
+    const int part = blockIdx.x % wgs_per_page;
+    const int64_t dst_page = page_ids[page];
+    const u32x4 *src = host_pages + (int64_t)page * page_chunks;
+    u32x4 *dst = pool + dst_page * page_chunks;
+    const int base = part * SWAP_CHUNKS + threadIdx.x;
+    u32x4 v[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int c = base + i * 256;
+        if (c < page_chunks) v[i] = __builtin_nontemporal_load(src + c);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int c = base + i * 256;
+        if (c < page_chunks) dst[c] = v[i];
+    }
+}
+
+hipError_t launch_swap_in(const void *host_pages, const int32_t *page_ids_dev, int32_t n_pages,
+                          void *kv_pool, int64_t page_bytes, hipStream_t s) {
+    if (n_pages == 0) return hipSuccess;
+    const int page_chunks = (int)(page_bytes / 16);
+    const int wgs_per_page = (page_chunks + SWAP_CHUNKS - 1) / SWAP_CHUNKS;
+    hipLaunchKernelGGL(swap_in_kernel, dim3((unsigned)n_pages * wgs_per_page), dim3(256), 0, s,
+                       (const u32x4 *)host_pages, page_ids_dev, (u32x4 *)kv_pool, page_chunks,
+                       wgs_per_page);
+    return hipGetLastError();
+}
+
+}  // namespace pbkv

@@ -1,0 +1,259 @@
+"""GPU parity: the HIP path, called through the C boundary, against the fp64 oracle.
+
+Tolerances (written here, derived in the design doc): bf16 max abs error 2e-2 and relative
+L2 error 1e-2; fp32 max abs error 1e-5 and relative L2 error 1e-5.  Append and swap-in
+are byte moves and must be bit-exact.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from paper_2605_06472_amd import binding                      # noqa: E402
+from paper_2605_06472_amd import workloads as W               # noqa: E402
+from tests import bruteforce                                  # noqa: E402
+from tests.gpu_util import DeviceBatch, assert_close, sample_rows, to_numpy, to_torch   # noqa: E402
+
+
+def _oracle(oracle, b, rows=None):
+    return oracle.prefill(b.q, b.k_new, b.v_new, b.kv_pool, b.block_table, b.prefix_lens,
+                          b.new_lens, rows=rows)
+
+
+def _check_full(oracle, b, what):
+    print("case", what, "B", b.B, "N", b.N, flush=True)
+    db = DeviceBatch(b)
+    db.prefill()
+    torch.cuda.synchronize()
+    got = db.out_f64()
+    want = _oracle(oracle, b)
+    return assert_close(got, want, b.dtype, what)
+
+
+# ------------------------------------------------------------------ small, element by element
+def test_cfg0_tiny_fp32(oracle):
+    b = W.tiny_fp32()
+    _check_full(oracle, b, "cfg0")
+    db = DeviceBatch(b)
+    db.prefill()
+    torch.cuda.synchronize()
+    ref, _ = bruteforce.attention(b)
+    assert_close(db.out_f64(), ref, "f32", "cfg0 vs contiguous brute force")
+
+
+RAGGED = {
+    "bf16_d128_g4": dict(dtype="bf16"),
+    "bf16_d128_g4_peaked": dict(dtype="bf16", q_scale=8.0),
+    "bf16_d64_g4": dict(dtype="bf16", d=64),
+    "bf16_d128_g1": dict(dtype="bf16", Hq=2, Hkv=2),
+    "bf16_d128_g2": dict(dtype="bf16", Hq=4, Hkv=2),
+    "bf16_d128_g8": dict(dtype="bf16", Hq=16, Hkv=2),
+    "bf16_d64_g16": dict(dtype="bf16", Hq=16, Hkv=1, d=64),
+    "bf16_shared_root": dict(dtype="bf16", shared_root=48, num_pages=96),
+    "bf16_tiles_and_tail": dict(dtype="bf16", prefix_lens=(300, 77, 1000, 0), new_lens=(200, 65, 130, 257),
+                                num_pages=256),
+    "f32_d64_g2": dict(dtype="f32", Hq=4, Hkv=2, d=64, sigma=1.0),
+    "f32_d128_g3": dict(dtype="f32", Hq=6, Hkv=2, d=128, sigma=1.0),
+    "f32_tiles_and_tail": dict(dtype="f32", Hq=2, Hkv=1, d=64, sigma=1.0, prefix_lens=(300, 77, 0),
+                               new_lens=(100, 65, 130), num_pages=128),
+}
+
+
+@pytest.mark.parametrize("name", sorted(RAGGED))
+def test_ragged_small_batches(oracle, name):
+    b = W.ragged_small(40, **RAGGED[name])
+    _check_full(oracle, b, name)
+
+
+def test_single_row_and_empty_requests(oracle):
+    b = W.ragged_small(41, "bf16", prefix_lens=(0, 0, 17, 64), new_lens=(1, 0, 1, 1))
+    _check_full(oracle, b, "single rows")
+    out = DeviceBatch(b)
+    out.prefill()
+    torch.cuda.synchronize()
+    # first row of an empty prefix returns its own value exactly (bf16 in, bf16 out)
+    G = b.Hq // b.Hkv
+    assert np.array_equal(to_numpy(out.out)[0], np.repeat(b.v_new[0], G, axis=0))
+
+
+def test_rows_of_other_calls_are_untouched(oracle):
+    b = W.ragged_small(42, "bf16")
+    db = DeviceBatch(b)
+    big = torch.full((b.N + 8, b.Hq, b.d), 3.0, dtype=torch.bfloat16, device="cuda")
+    db.prefill(out=big[4:4 + b.N])
+    torch.cuda.synchronize()
+    assert torch.all(big[:4] == 3.0) and torch.all(big[4 + b.N:] == 3.0)
+    assert_close(W.to_f64(to_numpy(big[4:4 + b.N])), _oracle(oracle, b), "bf16", "offset out")
+
+
+# ------------------------------------------------------------------ invariants on the GPU
+def test_page_permutation_is_bit_identical_on_gpu():
+    a = W.ragged_small(43, "bf16", prefix_lens=(300, 77, 1000, 0), new_lens=(200, 65, 130, 257),
+                       num_pages=256)
+    perm = np.random.default_rng(2).permutation(a.num_pages)
+    da = DeviceBatch(a)
+    da.prefill()
+    pool2 = np.empty_like(a.kv_pool)
+    pool2[perm] = a.kv_pool
+    dbb = DeviceBatch(a)
+    dbb.kv_pool = to_torch(pool2)
+    dbb.block_table = to_torch(perm[a.block_table].astype(np.int32))
+    dbb.prefill()
+    torch.cuda.synchronize()
+    assert torch.equal(da.out, dbb.out)
+
+
+def test_run_to_run_determinism():
+    b = W.shared_system_prompt(batch=2, prefix=512, new=200, num_pages=128)
+    db = DeviceBatch(b)
+    db.prefill()
+    first = db.out.clone()
+    for _ in range(3):
+        db.out.zero_()
+        db.prefill()
+        assert torch.equal(first, db.out)
+
+
+def test_prefix_reuse_equals_from_scratch_on_gpu(oracle):
+    """Same token sequence, once with a cached prefix and once as a full prefill."""
+    b = W.ragged_small(44, "bf16", prefix_lens=(200,), new_lens=(120,), num_pages=64)
+    L = 320
+    K, V = b.logical_k[0], b.logical_v[0]
+    qfull = W.normal_tensor(78, 0, (L, b.Hq, b.d), 2 ** -0.5, "bf16")
+    qfull[200:] = b.q
+    scratch = W.Batch(name="scratch", dtype="bf16", Hq=b.Hq, Hkv=b.Hkv, d=b.d, P=b.P,
+                      num_pages=b.num_pages, q=qfull, k_new=np.ascontiguousarray(K),
+                      v_new=np.ascontiguousarray(V), kv_pool=b.kv_pool,
+                      block_table=np.zeros((1, 20), np.int32), prefix_lens=np.array([0], np.int32),
+                      new_lens=np.array([L], np.int32))
+    d1, d2 = DeviceBatch(b), DeviceBatch(scratch)
+    d1.prefill()
+    d2.prefill()
+    torch.cuda.synchronize()
+    want = _oracle(oracle, b)
+    assert_close(d1.out_f64(), want, "bf16", "reuse")
+    assert_close(d2.out_f64()[200:], want, "bf16", "from scratch")
+    # the two GPU results agree with each other far inside the oracle tolerance
+    assert np.abs(d1.out_f64() - d2.out_f64()[200:]).max() <= 1e-2
+
+
+# ------------------------------------------------------------------ append / swap-in: bit-exact
+@pytest.mark.parametrize("dtype,kw", [("bf16", {}), ("bf16", dict(d=64, Hq=4, Hkv=4)),
+                                      ("f32", dict(d=64, Hq=2, Hkv=1, sigma=1.0))])
+def test_append_is_bit_exact(oracle, dtype, kw):
+    b = W.ragged_small(50, dtype, **kw)
+    db = DeviceBatch(b)
+    db.append()
+    torch.cuda.synchronize()
+    want = oracle.append_kv(b.k_new, b.v_new, b.kv_pool, b.block_table, b.prefix_lens, b.new_lens)
+    assert np.array_equal(to_numpy(db.kv_pool), want)
+    assert not np.array_equal(want, b.kv_pool)
+
+
+def test_swap_in_is_bit_exact_and_restores_attention(oracle):
+    b = W.ragged_small(51, "bf16", prefix_lens=(48, 100, 333), new_lens=(3, 9, 40), nonresident=(2, 5, 11),
+                       num_pages=96)
+    db = DeviceBatch(b)
+    db.swap_in()
+    torch.cuda.synchronize()
+    want_pool = oracle.swap_in(b.host_pages, b.swap_page_ids, b.kv_pool)
+    assert np.array_equal(to_numpy(db.kv_pool), want_pool)
+    db.prefill()
+    torch.cuda.synchronize()
+    ref, _ = bruteforce.attention(b)
+    assert_close(db.out_f64(), ref, "bf16", "after swap-in")
+
+
+def test_append_on_side_stream_overlaps_attention(oracle):
+    b = W.ragged_small(52, "bf16", prefix_lens=(300, 77, 1000, 5), new_lens=(200, 65, 130, 257), num_pages=256)
+    db = DeviceBatch(b)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    db.append(stream=side)
+    db.prefill()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    assert_close(db.out_f64(), _oracle(oracle, b), "bf16", "attention beside append")
+    want = oracle.append_kv(b.k_new, b.v_new, b.kv_pool, b.block_table, b.prefix_lens, b.new_lens)
+    assert np.array_equal(to_numpy(db.kv_pool), want)
+
+
+# ------------------------------------------------------------------ full-size configurations
+def _check_sampled(oracle, b, what, per_request=4):
+    print("case", what, "B", b.B, "N", b.N, "flops %.3g" % b.attention_flops(), flush=True)
+    db = DeviceBatch(b)
+    db.prefill()
+    torch.cuda.synchronize()
+    rows = sample_rows(b, per_request=per_request)
+    got = db.out_f64()
+    assert np.isfinite(got).all()
+    want = _oracle(oracle, b, rows=rows)
+    err, rel = assert_close(got[rows], want, b.dtype, what)
+    print(what, "rows checked", len(rows), "max abs err %.3e rel L2 %.3e" % (err, rel), flush=True)
+    return db
+
+
+@pytest.mark.parametrize("q_scale", [1.0, 8.0])
+def test_cfg1_shared_system_prompt(oracle, q_scale):
+    b = W.shared_system_prompt(q_scale=q_scale)
+    _check_sampled(oracle, b, "cfg1 q_scale=%g" % q_scale, per_request=8)
+
+
+@pytest.mark.parametrize("q_scale", [1.0, 8.0])
+def test_cfg2_dynamic_workflow(oracle, q_scale):
+    b = W.dynamic_workflow_batch(q_scale=q_scale)
+    _check_sampled(oracle, b, "cfg2 q_scale=%g" % q_scale)
+
+
+def test_cfg3_long_history(oracle):
+    b = W.long_history()
+    _check_sampled(oracle, b, "cfg3", per_request=2)
+
+
+def test_cfg4_mixed_hit_miss_with_swap_in(oracle):
+    """Pages of the host tier are swapped in on a side stream, group by group, while the
+    main stream attends to the requests whose pages have landed; then the suffix KV is
+    appended.  Pool content and attention output are checked against the oracle."""
+    b = W.mixed_hit_miss()
+    print("case cfg4 B", b.B, "N", b.N, "swap pages", b.host_pages.shape[0], flush=True)
+    db = DeviceBatch(b)
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    order = np.argsort(np.diff(b.swap_offsets), kind="stable")      # fewest missing pages first
+    # the C calls take contiguous request ranges, so each group is a set of single requests
+    off = np.concatenate([[0], np.cumsum(b.new_lens)]).astype(np.int64)
+    side.wait_stream(main)
+    for grp in np.array_split(order, 4):
+        for r in grp:
+            lo, hi = int(b.swap_offsets[r]), int(b.swap_offsets[r + 1])
+            if hi > lo:
+                binding.swap_in_pages(db.shape, db.host_pages[lo:hi], b.swap_page_ids[lo:hi], db.kv_pool, side)
+        ev = torch.cuda.Event()
+        ev.record(side)
+        main.wait_event(ev)
+        for r in grp:
+            sl = slice(int(off[r]), int(off[r + 1]))
+            binding.prefix_prefill(db.sub_shape(1), db.q[sl], db.k_new[sl], db.v_new[sl], db.kv_pool,
+                                   db.block_table[r:r + 1], b.prefix_lens[r:r + 1], b.new_lens[r:r + 1],
+                                   db.out[sl], main)
+    done = torch.cuda.Event()
+    done.record(main)
+    side.wait_event(done)
+    db.append(stream=side)
+    torch.cuda.synchronize()
+    resident = oracle.swap_in(b.host_pages, b.swap_page_ids, b.kv_pool)
+    rows = sample_rows(b, per_request=1)
+    want = oracle.prefill(b.q, b.k_new, b.v_new, resident, b.block_table, b.prefix_lens, b.new_lens, rows=rows)
+    err, rel = assert_close(db.out_f64()[rows], want, "bf16", "cfg4")
+    print("cfg4 rows checked", len(rows), "max abs err %.3e rel L2 %.3e" % (err, rel), flush=True)
+    final = oracle.append_kv(b.k_new, b.v_new, resident, b.block_table, b.prefix_lens, b.new_lens)
+    assert np.array_equal(to_numpy(db.kv_pool), final)
+
+
+def test_pageable_host_memory_is_rejected():
+    b = W.ragged_small(53, "bf16", prefix_lens=(48,), new_lens=(3,), nonresident=(2,))
+    db = DeviceBatch(b)
+    pageable = to_torch(b.host_pages, "cpu", pin=False)
+    with pytest.raises(binding.PbkvError) as e:
+        binding.swap_in_pages(db.shape, pageable, b.swap_page_ids, db.kv_pool)
+    assert e.value.code == -6
