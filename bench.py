@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the prefix-reuse prefill hot path on one MI355X.
+
+A step = one pass of the hot path over one synthetic batch, inputs resident in HBM:
+prefix-reuse prefill attention on the main stream, the paged KV append of the same
+suffix on a side stream (overlapped, joined at the end of the step) and, for the
+mixed hit/miss workload, the host->pool page swap-in that must land first.
+Prints ONE JSON line on stdout.
+"""
+import argparse
+import ctypes
+import json
+import os
+import re
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def _profile_traffic(workload):
+    """HBM bytes per attention launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+    as recorded in the committed profile summary for this workload; None if absent."""
+    path = os.path.join(ROOT, "profiles", "attn_bf16_%s_pmc.txt" % workload)
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+class Step:
+    """Pre-marshalled C calls for one batch (marshalling only; the work is in the kernels)."""
+
+    def __init__(self, db, torch, binding):
+        b = db.b
+        self.db, self.torch = db, torch
+        self.lib = binding.load()
+        self.shape = ctypes.byref(db.shape)
+        vp = ctypes.c_void_p
+        self.pl = np.ascontiguousarray(b.prefix_lens, np.int32)
+        self.nl = np.ascontiguousarray(b.new_lens, np.int32)
+        self.args_prefill = [vp(t.data_ptr()) for t in (db.q, db.k_new, db.v_new, db.kv_pool, db.block_table)]
+        self.plp, self.nlp = vp(self.pl.ctypes.data), vp(self.nl.ctypes.data)
+        self.outp = vp(db.out.data_ptr())
+        self.main = torch.cuda.current_stream()
+        self.side = torch.cuda.Stream()
+        self.mainp, self.sidep = vp(self.main.cuda_stream), vp(self.side.cuda_stream)
+        self.join = torch.cuda.Event()
+        self.fork = torch.cuda.Event()
+
+    def attention(self):
+        rc = self.lib.pbkv_prefix_prefill(self.shape, *self.args_prefill, self.plp, self.nlp, self.outp, self.mainp)
+        assert rc == 0, self.lib.pbkv_last_error()
+
+    def append(self):
+        a = self.args_prefill
+        rc = self.lib.pbkv_append_kv(self.shape, a[1], a[2], a[3], a[4], self.plp, self.nlp, self.sidep)
+        assert rc == 0, self.lib.pbkv_last_error()
+
+    def run(self, ev0=None, ev1=None):
+        self.fork.record(self.main)
+        self.side.wait_event(self.fork)
+        self.append()
+        if ev0 is not None:
+            ev0.record(self.main)
+        self.attention()
+        if ev1 is not None:
+            ev1.record(self.main)
+        self.join.record(self.side)
+        self.main.wait_event(self.join)
+
+
+def time_config(name, steps, warmup, torch, binding, W, DeviceBatch):
+    b = W.CONFIGS[name]()
+    db = DeviceBatch(b)
+    if b.host_pages is not None:            # make every prefix page resident before timing attention
+        db.swap_in()
+    st = Step(db, torch, binding)
+    for _ in range(warmup):
+        st.run()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        st.run(*evs[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = float(np.mean([a.elapsed_time(c) for a, c in evs]))
+    return b, db, wall, kern_ms
+
+
+def swap_in_rate(db, torch, binding, reps=3):
+    """Host->pool swap-in of every host-tier page of the batch, GB/s (best of reps)."""
+    b = db.b
+    best = None
+    for _ in range(reps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        db.swap_in()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    return b.host_pages.nbytes / best / 1e9, best
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--config", default="cfg1", choices=["cfg1", "cfg2", "cfg3", "cfg4"])
+    ap.add_argument("--no-extra", action="store_true", help="skip the other workloads and the CPU baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_06472_amd import binding
+    from paper_2605_06472_amd import workloads as W
+    from tests.gpu_util import DeviceBatch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    binding.load()
+
+    b, db, wall, kern_ms = time_config(args.config, args.steps, args.warmup, torch, binding, W, DeviceBatch)
+    ms_per_step = wall / args.steps * 1e3
+    flops = b.attention_flops()
+    tflops_kernel = flops / (kern_ms * 1e-3) / 1e12
+    line = {
+        "metric": "prefix-reuse prefill new tokens/s + TFLOP/s (MFMA util %), 8B-class GQA",
+        "value": b.N / (ms_per_step * 1e-3),
+        "unit": "new tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": b.name, "batch": b.B, "new_tokens": b.N,
+                   "prefix_lens": [int(b.prefix_lens.min()), int(b.prefix_lens.max())],
+                   "heads_q_kv": [b.Hq, b.Hkv], "head_dim": b.d, "page_size": b.P,
+                   "step": "attention (main stream) + paged append (side stream), one layer"},
+        "tflops_step": flops / (ms_per_step * 1e-3) / 1e12,
+        "mfma_util_step": flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": tflops_kernel,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops_kernel / PEAK_BF16_TFLOPS,
+                     "flops_per_launch": flops, "avg_launch_ms": kern_ms,
+                     "traffic": _profile_traffic(args.config),
+                     "algorithmic_bytes_per_launch": b.attention_bytes()},
+        "paper_context": "PBKV end-to-end workflow latency 1.85x vs LRU and 1.26x vs KVFlow on 8x A6000 "
+                         "(SGLang + HiCache, Qwen3-14B/32B); cache-policy numbers, not a kernel baseline",
+    }
+
+    if not args.no_extra:
+        import oracle
+        # CPU baseline: the oracle as it stands on this host's cores, bounded sample of the same workload
+        rows_all = np.arange(b.N, dtype=np.int64)
+        probe = np.linspace(0, b.N - 1, 32).astype(np.int64)
+        t0 = time.perf_counter()
+        oracle.prefill(b.q, b.k_new, b.v_new, b.kv_pool, b.block_table, b.prefix_lens, b.new_lens, rows=probe)
+        per_row = (time.perf_counter() - t0) / len(probe)
+        n_rows = int(min(b.N, max(32, 15.0 / per_row)))
+        rows = rows_all if n_rows == b.N else np.unique(np.linspace(0, b.N - 1, n_rows).astype(np.int64))
+        t0 = time.perf_counter()
+        oracle.prefill(b.q, b.k_new, b.v_new, b.kv_pool, b.block_table, b.prefix_lens, b.new_lens, rows=rows)
+        dt = time.perf_counter() - t0
+        line["cpu_baseline"] = {"value": len(rows) / dt, "unit": "new tokens/s", "cores": oracle.threads(),
+                                "kind": "oracle",
+                                "sample": "%d of %d suffix rows (evenly spaced, all %d query heads) of %s, %.1f s"
+                                          % (len(rows), b.N, b.Hq, b.name, dt)}
+        extra = {}
+        for name in ("cfg2", "cfg3", "cfg4"):
+            if name == args.config:
+                continue
+            try:
+                steps = 20 if name == "cfg2" else 5
+                b2, db2, wall2, k2 = time_config(name, steps, 2, torch, binding, W, DeviceBatch)
+                f2 = b2.attention_flops()
+                extra[name] = {"workload": b2.name, "new_tokens": b2.N, "ms_per_step": wall2 / steps * 1e3,
+                               "new_tokens_per_s": b2.N / (wall2 / steps),
+                               "attn_kernel_ms": k2, "attn_tflops": f2 / (k2 * 1e-3) / 1e12,
+                               "attn_frac_of_bf16_peak": f2 / (k2 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+                if b2.host_pages is not None:
+                    gbs, secs = swap_in_rate(db2, torch, binding)
+                    extra[name].update({"swap_in_GBps": gbs, "swap_in_bytes": int(b2.host_pages.nbytes),
+                                        "swap_in_ms": secs * 1e3})
+                del db2, b2
+                torch.cuda.empty_cache()
+            except Exception as e:                      # the headline line must still print
+                extra[name] = {"error": repr(e)}
+        line["extra"] = extra
+
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -29,7 +29,13 @@ def _bind(path):
                                            vp, vp, vp, vp, vp, vp]
         lib.pbkv_oracle_swap_in.restype = ctypes.c_int
         lib.pbkv_oracle_swap_in.argtypes = [i64, i64, vp, vp, i64, vp]
+        lib.pbkv_oracle_threads.restype = ctypes.c_int
     return lib
+
+
+def threads():
+    """Host threads the oracle's row loop uses."""
+    return int(_lib().pbkv_oracle_threads())
 
 
 def _lib():

@@ -32,7 +32,21 @@
 #include <stdlib.h>
 #include <string.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
 enum { ORACLE_BF16 = 0, ORACLE_F32 = 1 };
+
+/* Threads the row loop of pbkv_oracle_prefill runs on (rows are independent). */
+int pbkv_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* bf16 is the upper half of an IEEE binary32: widening is exact. */
 static double widen(const void *base, int64_t idx, int dtype)
