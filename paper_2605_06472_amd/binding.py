@@ -11,7 +11,7 @@ import os
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libpbkv.so")
+LIB_PATH = os.environ.get("PBKV_LIB", os.path.join(HERE, "libpbkv.so"))
 
 PBKV_BF16, PBKV_F32 = 0, 1
 STATUS = {0: "PBKV_OK", -1: "PBKV_ERR_NULL", -2: "PBKV_ERR_SHAPE", -3: "PBKV_ERR_DTYPE",
