@@ -3,7 +3,7 @@
 // 32x32x16 bf16 MFMA, fp32 accumulation.
 //
 // Work decomposition
-//   work-group = 4 waves = (request, KV head, block of suffix tokens).  The query heads
+//   work-group = NW waves = (request, KV head, block of suffix tokens).  The query heads
 //   of a GQA group share every K/V tile staged in LDS: wave w takes query head
 //   w % Gw (Gw = min(G,4)) and token sub-block w / Gw, 32*QB tokens per wave.
 //   blockIdx -> KV head is the fastest index, so with round-robin dispatch over the 8
@@ -21,19 +21,23 @@
 //   row-major [key][d] tile.
 //
 // Page gather
-//   K/V rows go from global memory straight into LDS (global_load_lds_dwordx4, 16 bytes
-//   per lane, 1 KiB contiguous in LDS per wave instruction) -- no staging registers and
-//   no LDS store instructions.  Rows are unpadded; bank conflicts are avoided by an XOR
-//   swizzle of the 16-byte chunk index that is applied on the global-address side:
+//   K/V rows go from global memory straight into LDS (buffer_load_dwordx4 ... lds, 16
+//   bytes per lane, 1 KiB contiguous in LDS per wave instruction) -- no staging registers
+//   and no LDS store instructions.  Rows are unpadded; bank conflicts are avoided by an
+//   XOR swizzle of the 16-byte chunk index that is applied on the global-address side:
 //   the lane that owns LDS chunk position c' of row r fetches global chunk c'^swz(r).
 //
-// Software pipeline (one wave does both MFMA and VALU work; the two are interleaved
-// with scheduling-group barriers):
-//   phase A   S(j+1) = K(j+1) Q^T  on the MFMA  ||  P(j) = exp2(S(j) c - m c), row sums
-//   phase B   O += V(j)^T P(j)     on the MFMA  ||  row max of S(j+1)
-// so K runs one tile ahead of V, and the score registers ping-pong between two sets.
+// Software pipeline.  Measured on gfx950: the vector-ALU issue port, not the MFMA pipe,
+// limits a wave that mixes both (each MFMA costs ~11 port cycles, each VALU op 4, each
+// transcendental 8), so the softmax arithmetic is split evenly over the two MFMA phases:
+//   phase A   S(j+1) = K(j+1) Q^T on the MFMA  ||  P(j) = exp2(t(j)), row sums, bf16 pack
+//   phase B   O += V(j)^T P(j)    on the MFMA  ||  t(j+1) = S(j+1) c - M, row max of t
+// where M is the running reference maximum in log2 units.  K runs one tile ahead of V,
+// and the score registers ping-pong between two sets.  The reference is only moved
+// (and O rescaled) when a row maximum exceeds it by more than 2^8.
 #include "pbkv_internal.h"
 
+#include <cstdio>
 #include <cstdlib>
 
 namespace pbkv {
@@ -49,8 +53,9 @@ typedef __attribute__((address_space(3))) void lds_void;
 constexpr int BN = 64;   // keys per LDS tile (two 32-key MFMA row blocks)
 constexpr int KB = BN / 32;
 constexpr int PF = 3;    // LDS operand prefetch distance, in pipeline steps
+constexpr float RESCALE_LOG2 = 8.0f;   // the reference maximum may lag by this much (log2)
 
-template <int D>
+template <int D, int NW>
 struct Geom {
     static constexpr int DC = D / 16;         // contraction steps of QK^T per key block
     static constexpr int DB = D / 32;         // 32-row blocks of O^T
@@ -59,7 +64,8 @@ struct Geom {
     static constexpr int TILEB = BN * ROWB;   // bytes per K or V tile
     static constexpr int CPR = D / 8;         // 16-byte chunks per row
     static constexpr int RPI = 64 / CPR;      // rows covered by one wave-wide 1 KiB load
-    static constexpr int NI = BN / (4 * RPI); // loads per wave per tile
+    static constexpr int NI = BN / (NW * RPI);// loads per wave per tile
+    static_assert(NI >= 1, "too many waves for this tile");
     // XOR applied to the chunk index of row `row` (conflict-free ds_read_b128 of 16
     // consecutive rows for K; conflict-free 4-row x 32-byte transposing reads for V)
     static __device__ __forceinline__ int swz_k(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
@@ -75,27 +81,33 @@ static __device__ __forceinline__ float xsum32(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// Query blocks (of 32 rows) per wave: 2 = one wave per SIMD with 64 rows each, 1 = two
-// work-groups per CU with 32 rows per wave.
-static int query_blocks() {
-    static int qb = [] {
-        const char *e = getenv("PBKV_ATTN_QB");
-        return (e && e[0] == '1') ? 1 : 2;
+// Launch shape, "QN": Q = 32-row query blocks per wave, N = waves per work-group.
+//   14: 4 waves x 32 rows, two work-groups per CU (default)
+//   18: 8 waves x 32 rows, two waves per SIMD share one set of K/V tiles
+//   24: 4 waves x 64 rows, one wave per SIMD
+static int launch_shape() {
+    static int v = [] {
+        const char *e = getenv("PBKV_ATTN_SHAPE");
+        const int x = e ? atoi(e) : 14;
+        return (x == 18 || x == 24) ? x : 14;
     }();
-    return qb;
+    return v;
 }
 
 int attn_bf16_tile_tokens(int /*head_dim*/, int group) {
     const int gw = group < 4 ? group : 4;
-    return 32 * query_blocks() * (4 / gw);
+    const int s = launch_shape();
+    return 32 * (s / 10) * ((s % 10) / gw);
 }
 
 // Keeps a value (and so the code that computes it) at this point of the program; the
 // constraint names a vector register, which only exists in the device pass.
 #if defined(__HIP_DEVICE_COMPILE__)
 #define PIN_V(x) asm volatile("" : "+v"(x))
+#define PIN_A(x) asm volatile("" : "+a"(x))   // accumulation register: usable only by the MFMA
 #else
 #define PIN_V(x) (void)(x)
+#define PIN_A(x) (void)(x)
 #endif
 
 // scheduling-group masks
@@ -103,13 +115,15 @@ int attn_bf16_tile_tokens(int /*head_dim*/, int group) {
 #define SG_MFMA 0x008
 #define SG_DSRD 0x100
 
-template <int D, int QB>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3 - QB, 3 - QB)))
+template <int D, int QB, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(3 - QB, 3 - QB)))
 void attn_bf16_kernel(AttnParams p, int G, int Gw) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the body uses gfx950-only builtins and types; the host pass only needs the stub
-    using Gm = Geom<D>;
+    using Gm = Geom<D, NW>;
     constexpr int NS = Gm::NS;
+    constexpr int NT = 64 * NW;
     constexpr int SPS = QB * 32 / NS;     // scores per lane handled in one pipeline step
+
     static_assert(SPS >= 2 && SPS % 2 == 0, "scores are converted in pairs");
     // four separate arrays: the direct-to-LDS loads of one buffer provably do not alias
     // the operand reads of the others
@@ -127,12 +141,15 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
     const TileDesc td = p.tiles[rest / nsplit];
     const int head = kvh * G + split * Gw + (w % Gw);
     constexpr int WTOK = 32 * QB;
-    const int tile_tok = WTOK * (4 / Gw);
+    const int tile_tok = WTOK * (NW / Gw);
     const int tok_base = td.tok0 + (w / Gw) * WTOK;
     const int tok_end = min(td.tok0 + tile_tok, td.new_len);
-    const int n_keys = td.prefix_len + tok_end;          // keys visible to the tile's last row
-    const int n_tiles = (n_keys + BN - 1) / BN;
-    const int wave_min_limit = td.prefix_len + min(tok_base, td.new_len - 1);
+    // KV tiles: TP tiles over the cached prefix (the last may be partial), then tiles over
+    // the suffix starting at its first token, so that every tile is read either through
+    // the block table or from k_new / v_new, never both.
+    const int TP = (td.prefix_len + BN - 1) / BN;
+    const int n_tiles = TP + (tok_end + BN - 1) / BN;
+    const int wave_min_tok = min(tok_base, td.new_len - 1);   // smallest token index in this wave
 
     const __bf16 *qg = (const __bf16 *)p.q;
     const __bf16 *kn = (const __bf16 *)p.k_new;
@@ -142,21 +159,21 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
 
     // zero the V buffers once: rows past the last key are never loaded, and 0 * stale bits
     // must not be able to produce a NaN in the PV product
-    for (int i = tid; i < Gm::TILEB / 16; i += 256) {
+    for (int i = tid; i < Gm::TILEB / 16; i += NT) {
         *(uint4 *)(sV0 + i * 16) = make_uint4(0, 0, 0, 0);
         *(uint4 *)(sV1 + i * 16) = make_uint4(0, 0, 0, 0);
     }
 
     // ---- Q^T operands: lane (li, lh) holds Q[token li][16*dc + 8*lh .. +7] -------------
     bf16x8 qreg[QB][Gm::DC];
-    int my_limit[QB];                                     // last visible key of this lane's row
+    int my_tokc[QB];                                      // this lane's token, clamped to the request
     int my_tok[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; qb++) {
         const int tr = tok_base + 32 * qb + li;
         my_tok[qb] = tr;
         const int tok = min(tr, td.new_len - 1);
-        my_limit[qb] = td.prefix_len + tok;
+        my_tokc[qb] = tok;
         const __bf16 *qp = qg + ((td.row0 + tok) * p.Hq + head) * D + 8 * lh;
 #pragma unroll
         for (int dc = 0; dc < Gm::DC; dc++) qreg[qb][dc] = *(const bf16x8 *)(qp + dc * 16);
@@ -190,7 +207,10 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
     // One wave-wide load = RPI consecutive rows of one page (or of the suffix), 1 KiB.  The
     // source is addressed as a raw buffer: a wave-uniform descriptor built with scalar
     // arithmetic (page base, or the suffix row base) plus a per-lane byte offset that does
-    // not change from tile to tile, so the gather costs no vector address arithmetic.
+    // not change from tile to tile, so the gather costs no vector address arithmetic.  The
+    // descriptor's size is the valid part of the row group: lanes of rows past the prefix
+    // end / past the last visible token are out of range and read nothing.
+    // Row group g = i*NW + w of a tile (i = 0..NI-1) holds rows g*RPI .. g*RPI + RPI-1.
     const int ld_lrow = l / Gm::CPR;                       // row inside this wave's row group
     const int ld_cpos = l % Gm::CPR;                       // chunk position this lane fills
     const int ld_slot = ((w * Gm::RPI) & 15) + ld_lrow;    // slot inside the page (same for all groups)
@@ -198,58 +218,52 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
     const int ld_cv = ld_cpos ^ Gm::swz_v(w * Gm::RPI + ld_lrow);   // ... (V)
     const int row_pitch = p.Hkv * Gm::ROWB;                // bytes between suffix tokens
     const int voff_pk = ld_slot * Gm::ROWB + ld_ck * 16;
-    const int voff_pv = ld_slot * Gm::ROWB + ld_cv * 16 + p.Hkv * 16 * Gm::ROWB;
+    const int voff_pv = ld_slot * Gm::ROWB + ld_cv * 16;
     const int voff_sk = ld_lrow * row_pitch + ld_ck * 16;
     const int voff_sv = ld_lrow * row_pitch + ld_cv * 16;
     const int page_bytes = 2 * p.Hkv * 16 * Gm::ROWB;
-    const char *pool_head = (const char *)pool + (int64_t)kvh * 16 * Gm::ROWB;
+    const char *pool_k = (const char *)pool + (int64_t)kvh * 16 * Gm::ROWB;    // K rows of this head in page 0
+    const char *pool_v = pool_k + (int64_t)p.Hkv * 16 * Gm::ROWB;             // V rows
     constexpr int RSRC_FLAGS = 0x00020000;                 // raw buffer, 32-bit data format
-    auto load_tile = [&](int k0, const PageIds &pid, char *buf, const __bf16 *fresh, bool is_v) {
-        const int voff_p = is_v ? voff_pv : voff_pk, voff_s = is_v ? voff_sv : voff_sk;
-        if (k0 + BN <= td.prefix_len) {
-            // the whole tile lies in the cached prefix: one descriptor per page
+    // page (inside the tile) of row group i*NW + w: the NW groups of one pass cover
+    // NW*RPI/16 consecutive pages, GPP groups per page
+    constexpr int GPP = 16 / Gm::RPI;
+    static_assert(NW % GPP == 0, "the waves of one pass cover whole pages");
+    constexpr int RUN = NW / GPP;                          // pages per pass
+    auto group_page = [&](const PageIds &pid, int i) {
+        int pg = pid.v[(i * RUN) % (BN / 16)];
+#pragma unroll
+        for (int r = 1; r < RUN; r++)
+            if (w / GPP == r) pg = pid.v[(i * RUN + r) % (BN / 16)];
+        return pg;
+    };
+    auto load_tile = [&](int t, const PageIds &pid, char *buf, const __bf16 *fresh, bool is_v) {
+        if (t < TP) {
+            // rows of logical pages 4t .. 4t+3, valid up to the prefix end
 #pragma unroll
             for (int i = 0; i < Gm::NI; i++) {
-                // page of this row group inside the tile: i for d=128, 2i + w/2 for d=64
-                const int pg = Gm::RPI == 4 ? pid.v[i] : ((w >> 1) ? pid.v[(2 * i + 1) % (BN / 16)] : pid.v[(2 * i) % (BN / 16)]);
-                const auto rsrc = __builtin_amdgcn_make_buffer_rsrc(
-                    (void *)(pool_head + (int64_t)pg * page_bytes), 0, page_bytes, RSRC_FLAGS);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(buf + (i * 4 + w) * 1024), 16, voff_p, 0, 0, 0);
+                const int lp = t * (BN / 16) + (i * RUN) % (BN / 16) + (w / GPP) % RUN;
+                const int prows = max(td.prefix_len - lp * 16, 0);     // >= 16: the whole page (no lane reaches further)
+                const char *pbase = (is_v ? pool_v : pool_k) + (int64_t)group_page(pid, i) * page_bytes;
+                const auto rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)pbase, 0, prows * Gm::ROWB, RSRC_FLAGS);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(buf + (i * NW + w) * 1024), 16,
+                                                         is_v ? voff_pv : voff_pk, 0, 0, 0);
             }
-            asm volatile("; tile from prefix pages");   // distinct block ends: keeps the three paths' loads apart
-        } else if (k0 >= td.prefix_len && k0 + BN <= n_keys) {
-            // the whole tile lies in the suffix: one descriptor, a scalar offset per row group
-            const char *base = (const char *)fresh + ((td.row0 + (k0 - td.prefix_len)) * p.Hkv + kvh) * (int64_t)Gm::ROWB;
-            const auto rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, BN * row_pitch, RSRC_FLAGS);
-#pragma unroll
-            for (int i = 0; i < Gm::NI; i++)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(buf + (i * 4 + w) * 1024), 16, voff_s,
-                                                         (i * 4 + w) * Gm::RPI * row_pitch, 0, 0);
-            asm volatile("; tile from the suffix");
+            asm volatile("; tile from prefix pages");   // distinct block ends keep the two paths' loads apart
         } else {
-            // the prefix ends inside this tile, or the tile holds the last visible keys
+            // RPI suffix tokens per row group, valid up to the last visible token
+            const int sb = (t - TP) * BN + w * Gm::RPI;    // this wave's first token in pass 0
+            const char *sbase = (const char *)fresh + ((td.row0 + sb) * p.Hkv + kvh) * (int64_t)Gm::ROWB;
 #pragma unroll
             for (int i = 0; i < Gm::NI; i++) {
-                const int g0 = k0 + (i * 4 + w) * Gm::RPI;    // first key of this wave's row group
-                if (g0 >= n_keys) continue;
-                lds_void *dst = (lds_void *)(buf + (i * 4 + w) * 1024);
-                const int pg = Gm::RPI == 4 ? pid.v[i] : ((w >> 1) ? pid.v[(2 * i + 1) % (BN / 16)] : pid.v[(2 * i) % (BN / 16)]);
-                const int split = td.prefix_len - g0;          // rows [0, split) of the group are prefix rows
-                if (split > 0) {
-                    const auto rp = __builtin_amdgcn_make_buffer_rsrc(
-                        (void *)(pool_head + (int64_t)pg * page_bytes), 0, page_bytes, RSRC_FLAGS);
-                    if (ld_lrow < split) __builtin_amdgcn_raw_ptr_buffer_load_lds(rp, dst, 16, voff_p, 0, 0, 0);
-                    asm volatile("; prefix rows of a mixed group");
-                }
-                if (split < Gm::RPI) {
-                    const char *sbase = (const char *)fresh +
-                                        ((td.row0 + (g0 - td.prefix_len)) * p.Hkv + kvh) * (int64_t)Gm::ROWB;
-                    const auto rs = __builtin_amdgcn_make_buffer_rsrc((void *)sbase, 0, Gm::RPI * row_pitch, RSRC_FLAGS);
-                    if (ld_lrow >= split && g0 + ld_lrow < n_keys)
-                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, dst, 16, voff_s, 0, 0, 0);
-                    asm volatile("; suffix rows of a mixed group");
-                }
+                const int srows = max(tok_end - (sb + i * NW * Gm::RPI), 0);   // >= RPI: the whole group
+                const int sbytes = srows > 0 ? (srows - 1) * row_pitch + Gm::ROWB : 0;
+                const auto rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                    (void *)(sbase + (int64_t)i * NW * Gm::RPI * row_pitch), 0, sbytes, RSRC_FLAGS);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(buf + (i * NW + w) * 1024), 16,
+                                                         is_v ? voff_sv : voff_sk, 0, 0, 0);
             }
+            asm volatile("; tile from the suffix");
         }
     };
 
@@ -261,9 +275,9 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
         for (int qb = 0; qb < QB; qb++)
 #pragma unroll
             for (int r = 0; r < 16; r++) O[db][qb][r] = 0.f;
-    float m_run[QB], m_new[QB], l_part[QB];
+    float M[QB], tmax[QB], l_part[QB];      // reference maximum (log2 units), max of pending t, row sum
 #pragma unroll
-    for (int qb = 0; qb < QB; qb++) { m_run[qb] = -INFINITY; m_new[qb] = -INFINITY; l_part[qb] = 0.f; }
+    for (int qb = 0; qb < QB; qb++) { M[qb] = 0.f; tmax[qb] = 0.f; l_part[qb] = 0.f; }
     const float c = 1.4426950408889634f * rsqrtf((float)D);
 
     // ---- per-lane LDS operand offsets (the swizzle makes them lane- and chunk-specific) ---
@@ -293,10 +307,17 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
         const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(vp + 8 * Gm::ROWB));
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
-    auto mask_scores = [&](f32x16 (&S)[KB][QB], int k0) {
+    // Tile t holds prefix keys 64t.. (valid below the prefix end) or suffix tokens
+    // 64(t-TP).. (valid up to the row's own token).  lim = last valid row of the tile for
+    // this lane's query row; needs_mask is wave-uniform.
+    auto needs_mask = [&](int t) {
+        return t < TP ? (t + 1) * BN > td.prefix_len : (t - TP) * BN + BN - 1 > wave_min_tok;
+    };
+    auto mask_scores = [&](f32x16 (&S)[KB][QB], int t) {
 #pragma unroll
         for (int qb = 0; qb < QB; qb++) {
-            const int rel = my_limit[qb] - k0 - 4 * lh;
+            const int lim = t < TP ? td.prefix_len - 1 - t * BN : my_tokc[qb] - (t - TP) * BN;
+            const int rel = lim - 4 * lh;
 #pragma unroll
             for (int kb = 0; kb < KB; kb++)
 #pragma unroll
@@ -305,7 +326,7 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
         }
     };
 
-    // ---- prologue: K(0), V(0), K(1) into LDS, S(0) and its row max ---------------------------
+    // ---- prologue: K(0), V(0), K(1) into LDS; S(0), its row max, t(0) -------------------------
     PageIds pid1, pid2;                                   // page ids of tiles j+1 and j+2
     __syncthreads();                                      // V buffers zeroed
     {
@@ -314,7 +335,7 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
         pid2 = fetch_page_ids(2);
         load_tile(0, pid0, sK0, kn, false);
         load_tile(0, pid0, sV0, vn, true);
-        load_tile(BN, pid1, sK1, kn, false);
+        load_tile(1, pid1, sK1, kn, false);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0): the loads have landed in LDS
     __syncthreads();
@@ -332,123 +353,148 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
         for (int qb = 0; qb < QB; qb++)
             Sa[s / Gm::DC][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][s % Gm::DC], Sa[s / Gm::DC][qb], 0, 0, 0);
     }
-    if (BN - 1 > wave_min_limit) mask_scores(Sa, 0);
+    if (needs_mask(0)) mask_scores(Sa, 0);
 #pragma unroll
     for (int qb = 0; qb < QB; qb++) {
+        // key 0 is visible to every row, so the first tile's row maximum is finite
         float mx = Sa[0][qb][0];
 #pragma unroll
         for (int kb = 0; kb < KB; kb++)
 #pragma unroll
             for (int r = 0; r < 16; r++) mx = fmaxf(mx, Sa[kb][qb][r]);
-        m_new[qb] = xmax32(mx);
+        M[qb] = xmax32(mx) * c;
+#pragma unroll
+        for (int kb = 0; kb < KB; kb++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) Sa[kb][qb][r] = fmaf(Sa[kb][qb][r], c, -M[qb]);
     }
 
-    // ---- one pipelined iteration: tile j, scores Sc = S(j) ready, Sn receives S(j+1) ----------
-    auto body = [&](int j, f32x16 (&Sc)[KB][QB], f32x16 (&Sn)[KB][QB], char *kread, char *vread,
+#ifdef PBKV_TRACE
+    unsigned long long tr_acc[6] = {0, 0, 0, 0, 0, 0};
+    unsigned long long tr_last = __builtin_amdgcn_s_memtime();
+    const unsigned long long tr_t0 = tr_last, tr_r0 = __builtin_amdgcn_s_memrealtime();
+#define TRACE_MARK(k) do { unsigned long long now_ = __builtin_amdgcn_s_memtime(); tr_acc[k] += now_ - tr_last; tr_last = now_; } while (0)
+#else
+#define TRACE_MARK(k) do {} while (0)
+#endif
+    // ---- one pipelined iteration: tile j; Tc = t(j) ready; Tn receives S(j+1), then t(j+1) ----
+    auto body = [&](int j, f32x16 (&Tc)[KB][QB], f32x16 (&Tn)[KB][QB], char *kread, char *vread,
                     char *kwrite, char *vwrite) __attribute__((always_inline)) {
-        // rescale lazily: a stale maximum is kept while it is within 2^8 of the true one
+        // move the reference only when a row maximum ran ahead of it by more than 2^8
+        TRACE_MARK(5);
         bool need = false;
 #pragma unroll
-        for (int qb = 0; qb < QB; qb++) need |= (m_new[qb] - m_run[qb]) * c > 8.0f;
+        for (int qb = 0; qb < QB; qb++) need |= tmax[qb] > RESCALE_LOG2;
         if (__any(need)) {
 #pragma unroll
             for (int qb = 0; qb < QB; qb++) {
-                const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new[qb]) * c);
-                m_run[qb] = m_new[qb];
+                const float d = fmaxf(tmax[qb], 0.f);      // never lower the reference
+                const float alpha = __builtin_amdgcn_exp2f(-d);
+                M[qb] += d;
                 l_part[qb] *= alpha;
 #pragma unroll
                 for (int db = 0; db < Gm::DB; db++)
 #pragma unroll
                     for (int r = 0; r < 16; r++) O[db][qb][r] *= alpha;
+#pragma unroll
+                for (int kb = 0; kb < KB; kb++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) Tc[kb][qb][r] -= d;
             }
         }
         // prefetch: page ids three tiles ahead, K two tiles ahead, V one tile ahead
         const PageIds pid3 = fetch_page_ids(j + 3);
-#ifndef ABL_NOLOAD
-        load_tile((j + 2) * BN, pid2, kwrite, kn, false);
-        load_tile((j + 1) * BN, pid1, vwrite, vn, true);
-#endif
-        float mc[QB], ls[QB];
+        float ls[QB];
 #pragma unroll
-        for (int qb = 0; qb < QB; qb++) { mc[qb] = m_run[qb] * c; ls[qb] = 0.f; }
+        for (int qb = 0; qb < QB; qb++) ls[qb] = 0.f;
         bf16x8 P[QB][KB][2];
 
-        // ---- phase A: S(j+1) = K(j+1) Q^T  ||  P = exp2(S(j) c - m c) ---------------------------
-        __builtin_amdgcn_sched_barrier(0);
+        // ---- phase A: S(j+1) = K(j+1) Q^T  ||  P = exp2(t(j)), row sums ---------------------------
+        // Two halves, each a scheduling region of its own, each preceded by half of the
+        // gather for the coming tiles (K(j+2), then V(j+1)): the loads are spread over the
+        // iteration instead of queueing behind the CU's 64 B/clk vector-memory port.
         bf16x8 kop[PF + 1];
 #pragma unroll
-        for (int s = 0; s < PF; s++) kop[s] = k_operand(kread, s);
-#pragma unroll
-        for (int s = 0; s < NS; s++) {
-            if (s + PF < NS) kop[(s + PF) % (PF + 1)] = k_operand(kread, s + PF);
-            const int kb = s / Gm::DC, dc = s % Gm::DC;
-#pragma unroll
-            for (int qb = 0; qb < QB; qb++) {
-#ifdef ABL_NOQK
-                if (dc == 0) Sn[kb][qb] = Sc[kb][qb];
-                continue;
+        for (int half = 0; half < 2; half++) {
+            __builtin_amdgcn_sched_barrier(0);
+#ifndef ABL_NOLOAD
+            if (half == 0) load_tile(j + 2, pid2, kwrite, kn, false);
+            else load_tile(j + 1, pid1, vwrite, vn, true);
 #endif
-                if (dc == 0) {
-                    f32x16 z;
+            __builtin_amdgcn_sched_barrier(0);
+            const int s0 = half * (NS / 2), s1 = s0 + NS / 2;
+            if (half == 0) {
 #pragma unroll
-                    for (int r = 0; r < 16; r++) z[r] = 0.f;
-                    Sn[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[s % (PF + 1)], qreg[qb][dc], z, 0, 0, 0);
-                } else {
-                    Sn[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[s % (PF + 1)], qreg[qb][dc], Sn[kb][qb], 0, 0, 0);
+                for (int s = 0; s < PF; s++) kop[s] = k_operand(kread, s);
+            }
+#pragma unroll
+            for (int s = s0; s < s1; s++) {
+                if (s + PF < NS) kop[(s + PF) % (PF + 1)] = k_operand(kread, s + PF);
+                const int kb = s / Gm::DC, dc = s % Gm::DC;
+#pragma unroll
+                for (int qb = 0; qb < QB; qb++) {
+                    if (dc == 0) {
+                        f32x16 z;
+#pragma unroll
+                        for (int r = 0; r < 16; r++) z[r] = 0.f;
+                        Tn[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[s % (PF + 1)], qreg[qb][dc], z, 0, 0, 0);
+                    } else {
+                        Tn[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[s % (PF + 1)], qreg[qb][dc], Tn[kb][qb], 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < SPS; t += 2) {
+                    const int idx = s * SPS + t;              // flattened (qb, kb, r)
+                    const int qb = idx / 32, kb2 = (idx % 32) / 16, r = idx % 16;
+                    f32x2 pv;
+                    pv[0] = __builtin_amdgcn_exp2f(Tc[kb2][qb][r]);
+                    pv[1] = __builtin_amdgcn_exp2f(Tc[kb2][qb][r + 1]);
+                    ls[qb] += pv[0];
+                    ls[qb] += pv[1];
+                    const bf16x2 pk = __builtin_convertvector(pv, bf16x2);
+                    P[qb][kb2][r / 8][r % 8] = pk[0];
+                    P[qb][kb2][r / 8][r % 8 + 1] = pk[1];
                 }
             }
+            // interleave: per MFMA its share of the exp work, one K operand read per step
+            if (half == 0) __builtin_amdgcn_sched_group_barrier(SG_DSRD, PF, 0);
 #pragma unroll
-            for (int t = 0; t < SPS; t += 2) {
-                const int idx = s * SPS + t;              // flattened (qb, kb, r)
-                const int qb = idx / 32, kb2 = (idx % 32) / 16, r = idx % 16;
-                f32x2 pv;
-#ifdef ABL_NOEXP
-                pv[0] = Sc[kb2][qb][r];
-                pv[1] = Sc[kb2][qb][r + 1];
-#else
-                pv[0] = __builtin_amdgcn_exp2f(fmaf(Sc[kb2][qb][r], c, -mc[qb]));
-                pv[1] = __builtin_amdgcn_exp2f(fmaf(Sc[kb2][qb][r + 1], c, -mc[qb]));
-                ls[qb] += pv[0];
-                ls[qb] += pv[1];
-#endif
-                const bf16x2 pk = __builtin_convertvector(pv, bf16x2);
-                P[qb][kb2][r / 8][r % 8] = pk[0];
-                P[qb][kb2][r / 8][r % 8 + 1] = pk[1];
+            for (int s = s0; s < s1; s++) {
+#pragma unroll
+                for (int qb = 0; qb < QB; qb++) {
+                    __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(SG_VALU, (5 * SPS) / (2 * QB), 0);
+                }
+                if (s + PF < NS) __builtin_amdgcn_sched_group_barrier(SG_DSRD, 1, 0);
             }
-        }
-        // interleave: per step, one K operand read, then per MFMA its share of the exp work
-        __builtin_amdgcn_sched_group_barrier(SG_DSRD, PF, 0);
+            // keep this half's probabilities and prefetched operands in this block (the
+            // probabilities are only consumed in phase B, and the optimiser would otherwise
+            // sink their computation out of the MFMA shadow)
 #pragma unroll
-        for (int s = 0; s < NS; s++) {
-#pragma unroll
-            for (int qb = 0; qb < QB; qb++) {
-                __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(SG_VALU, (7 * SPS) / (2 * QB), 0);
+            for (int idx = s0 * SPS; idx < s1 * SPS; idx += 8) {
+                const int qb = idx / 32, kb2 = (idx % 32) / 16, u = (idx % 16) / 8;
+                PIN_V(P[qb][kb2][u]);
             }
-            if (s + PF < NS) __builtin_amdgcn_sched_group_barrier(SG_DSRD, 1, 0);
-        }
-        // keep the probabilities in this block (they are only consumed in phase B, and the
-        // optimiser would otherwise sink their computation out of the MFMA shadow)
 #pragma unroll
-        for (int qb = 0; qb < QB; qb++) {
+            for (int qb = 0; qb < QB; qb++) PIN_V(ls[qb]);
+            if (half == 0) {
 #pragma unroll
-            for (int kb = 0; kb < KB; kb++) {
-                PIN_V(P[qb][kb][0]);
-                PIN_V(P[qb][kb][1]);
+                for (int s = 0; s < PF + 1; s++) PIN_V(kop[s]);
             }
-            PIN_V(ls[qb]);
         }
         __builtin_amdgcn_sched_barrier(0);
+        TRACE_MARK(1);
 #pragma unroll
         for (int qb = 0; qb < QB; qb++) l_part[qb] += ls[qb];
 
-        // ---- phase B: O += V(j)^T P  ||  row max of S(j+1) ----------------------------------------
-        const int k0n = (j + 1) * BN;
-        if (k0n + BN - 1 > wave_min_limit) mask_scores(Sn, k0n);
+        // ---- phase B: O += V(j)^T P  ||  t(j+1) = S(j+1) c - M and its row max --------------------
+        if (needs_mask(j + 1)) mask_scores(Tn, j + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        TRACE_MARK(2);
         __builtin_amdgcn_sched_barrier(0);
         float mx[QB];
 #pragma unroll
-        for (int qb = 0; qb < QB; qb++) mx[qb] = Sn[0][qb][0];
+        for (int qb = 0; qb < QB; qb++) mx[qb] = -INFINITY;
         bf16x8 vop[PF + 1];
 #pragma unroll
         for (int s = 0; s < PF; s++) vop[s] = v_operand(vread, s);
@@ -457,18 +503,15 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
             if (s + PF < NS) vop[(s + PF) % (PF + 1)] = v_operand(vread, s + PF);
             const int kb = s / (2 * Gm::DB), u = (s / Gm::DB) & 1, db = s % Gm::DB;
 #pragma unroll
-            for (int qb = 0; qb < QB; qb++) {
-#ifdef ABL_NOPV
-                if (s == 0) O[db][qb][0] += (float)P[qb][kb][u][0] + (float)vop[s % (PF + 1)][0];
-                continue;
-#endif
+            for (int qb = 0; qb < QB; qb++)
                 O[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[s % (PF + 1)], P[qb][kb][u], O[db][qb], 0, 0, 0);
-            }
 #pragma unroll
             for (int t = 0; t < SPS; t++) {
                 const int idx = s * SPS + t;
                 const int qb = idx / 32, kb2 = (idx % 32) / 16, r = idx % 16;
-                mx[qb] = fmaxf(mx[qb], Sn[kb2][qb][r]);
+                const float tv = fmaf(Tn[kb2][qb][r], c, -M[qb]);
+                Tn[kb2][qb][r] = tv;
+                mx[qb] = fmaxf(mx[qb], tv);
             }
         }
         __builtin_amdgcn_sched_group_barrier(SG_DSRD, 2 * PF, 1);
@@ -477,21 +520,27 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
 #pragma unroll
             for (int qb = 0; qb < QB; qb++) {
                 __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 1);
-                __builtin_amdgcn_sched_group_barrier(SG_VALU, (SPS + 3) / (2 * QB), 1);
+                __builtin_amdgcn_sched_group_barrier(SG_VALU, (3 * SPS) / (2 * QB), 1);
             }
             if (s + PF < NS) __builtin_amdgcn_sched_group_barrier(SG_DSRD, 2, 1);
         }
 #pragma unroll
-        for (int qb = 0; qb < QB; qb++) PIN_V(mx[qb]);
-        __builtin_amdgcn_sched_barrier(0);
+        for (int qb = 0; qb < QB; qb++) {
+            PIN_V(mx[qb]);
 #pragma unroll
-        for (int qb = 0; qb < QB; qb++) m_new[qb] = fmaxf(m_run[qb], xmax32(mx[qb]));
+            for (int kb = 0; kb < KB; kb++) PIN_V(Tn[kb][qb]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        TRACE_MARK(3);
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++) tmax[qb] = xmax32(mx[qb]);
         pid1 = pid2;
         pid2 = pid3;
 #ifndef ABL_NOBAR
         __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0): K(j+2), V(j+1) are in LDS
         __syncthreads();
 #endif
+        TRACE_MARK(4);
     };
 
     for (int j = 0; j < n_tiles; j += 2) {
@@ -499,6 +548,19 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
         if (j + 1 < n_tiles) body(j + 1, Sb, Sa, sK0, sV1, sK1, sV0);
     }
 
+#ifdef PBKV_TRACE
+    if (p.trace && l == 0 && w == 0 && blockIdx.x < 4096) {
+        unsigned long long *sp = (unsigned long long *)p.trace + 64 * 8 * 8 + blockIdx.x * 2;
+        sp[0] = tr_r0;
+        sp[1] = __builtin_amdgcn_s_memrealtime();
+    }
+    if (p.trace && l == 0 && blockIdx.x < 64) {
+        unsigned long long *tp = (unsigned long long *)p.trace + (blockIdx.x * NW + w) * 8;
+        for (int k = 0; k < 6; k++) tp[k] = tr_acc[k];
+        tp[6] = n_tiles;
+        tp[7] = ((__builtin_amdgcn_s_memtime() - tr_t0) << 24) | ((__builtin_amdgcn_s_memrealtime() - tr_r0) & 0xffffff);
+    }
+#endif
     // ---- epilogue: normalise, round once to bf16, store -----------------------------------
     // register r of O[db] is MFMA row 8*(r/4) + 4*lh + r%4; rows 0-15 are d = 16*db + row,
     // rows 16-31 are d = D/2 + 16*db + (row - 16)
@@ -522,20 +584,56 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
 #endif
 }
 
-template <int D, int QB>
+template <int D, int QB, int NW>
 static hipError_t launch_one(const AttnParams &p, int G, int Gw, hipStream_t s) {
     const unsigned grid = (unsigned)p.n_tiles * (G / Gw) * p.Hkv;
-    hipLaunchKernelGGL((attn_bf16_kernel<D, QB>), dim3(grid), dim3(256), 0, s, p, G, Gw);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, QB, NW>), dim3(grid), dim3(64 * NW), 0, s, p, G, Gw);
     return hipGetLastError();
 }
 
-hipError_t launch_attn_bf16(const AttnParams &p, int head_dim, hipStream_t s) {
+#ifdef PBKV_TRACE
+static void trace_dump(void *dev, int nw) {
+    static int calls = 0;
+    if (++calls != 3) return;
+    hipDeviceSynchronize();
+    static unsigned long long h[64 * 8 * 8 + 8192];
+    hipMemcpy(h, dev, sizeof h, hipMemcpyDeviceToHost);
+    {
+        unsigned long long *sp = h + 64 * 8 * 8, t0 = ~0ull, t1 = 0; int nb = 0;
+        for (int b = 0; b < 4096; b++) if (sp[2 * b]) { nb++; if (sp[2 * b] < t0) t0 = sp[2 * b]; if (sp[2 * b + 1] > t1) t1 = sp[2 * b + 1]; }
+        int late = 0; double sum_life = 0;
+        for (int b = 0; b < 4096; b++) if (sp[2 * b]) { if (sp[2 * b] - t0 > 2000) late++; sum_life += sp[2 * b + 1] - sp[2 * b]; }
+        printf("trace: %d blocks, span %.1f us, mean block life %.1f us, blocks starting >20us late: %d\n", nb, (t1 - t0) / 100.0, sum_life / nb / 100.0, late);
+        for (int b = 0; b < nb; b += nb / 16) printf("  block %d start %.1f end %.1f\n", b, (sp[2 * b] - t0) / 100.0, (sp[2 * b + 1] - t0) / 100.0);
+    }
+    const char *names[6] = {"top+loads", "phaseA", "between", "phaseB", "tail+barrier", "loop-carry"};
+    for (int b = 0; b < 64; b += 21)
+        for (int w = 0; w < nw; w += 3) {
+            unsigned long long *t = h + (b * nw + w) * 8;
+            printf("trace block %d wave %d tiles %llu:", b, w, t[6]);
+            for (int k = 0; k < 6; k++) printf(" %s=%.0f", names[k], t[6] ? (double)t[k] / t[6] : 0.0);
+            printf(" | life %llu ticks, %.1f us real, clock %.2f GHz", t[7] >> 24, (t[7] & 0xffffff) / 100.0, (t[7] >> 24) / ((t[7] & 0xffffff) * 10.0));
+            printf("\n");
+        }
+}
+#endif
+
+hipError_t launch_attn_bf16(const AttnParams &p0, int head_dim, hipStream_t s) {
+    AttnParams p = p0;
+#ifdef PBKV_TRACE
+    static void *trace_buf = nullptr;
+    if (!trace_buf) { hipMalloc(&trace_buf, (64 * 8 * 8 + 8192) * 8); hipMemset(trace_buf, 0, (64 * 8 * 8 + 8192) * 8); }
+    p.trace = trace_buf;
+    struct Dump { void *b; int nw; ~Dump() { trace_dump(b, nw); } } dump{trace_buf, launch_shape() % 10};
+#endif
     if (p.n_tiles == 0) return hipSuccess;
     const int G = p.Hq / p.Hkv;
     const int Gw = G < 4 ? G : 4;
-    if (query_blocks() == 1)
-        return head_dim == 128 ? launch_one<128, 1>(p, G, Gw, s) : launch_one<64, 1>(p, G, Gw, s);
-    return head_dim == 128 ? launch_one<128, 2>(p, G, Gw, s) : launch_one<64, 2>(p, G, Gw, s);
+    switch (launch_shape()) {
+        case 18: return head_dim == 128 ? launch_one<128, 1, 8>(p, G, Gw, s) : launch_one<64, 1, 8>(p, G, Gw, s);
+        case 24: return head_dim == 128 ? launch_one<128, 2, 4>(p, G, Gw, s) : launch_one<64, 2, 4>(p, G, Gw, s);
+        default: return head_dim == 128 ? launch_one<128, 1, 4>(p, G, Gw, s) : launch_one<64, 1, 4>(p, G, Gw, s);
+    }
 }
 
 }  // namespace pbkv

@@ -236,6 +236,7 @@ int pbkv_prefix_prefill(const pbkv_shape *s, const void *q, const void *k_new, c
     p.n_tiles = (int32_t)tiles.size();
     p.Hq = s->num_q_heads; p.Hkv = s->num_kv_heads;
     p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
+    p.trace = nullptr;
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = s->dtype == PBKV_BF16 ? pbkv::launch_attn_bf16(p, s->head_dim, st)
                                          : pbkv::launch_attn_f32(p, s->head_dim, st);

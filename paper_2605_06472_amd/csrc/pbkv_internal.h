@@ -35,6 +35,7 @@ struct AttnParams {
     const int32_t *block_table;
     const TileDesc *tiles;
     int32_t n_tiles, Hq, Hkv, max_pages, num_pages;
+    void *trace;   // development instrumentation; unused unless built with it
 };
 
 struct AppendParams {
