@@ -118,6 +118,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", default="cfg1", choices=["cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads and the CPU baseline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three 256 MiB device-to-device copies (known HBM traffic) so that a "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -134,6 +137,14 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     binding.load()
+
+    if args.calibrate_copy:
+        src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     b, db, wall, kern_ms = time_config(args.config, args.steps, args.warmup, torch, binding, W, DeviceBatch)
     ms_per_step = wall / args.steps * 1e3
@@ -193,8 +204,20 @@ def main():
                                "attn_frac_of_bf16_peak": f2 / (k2 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
                 if b2.host_pages is not None:
                     gbs, secs = swap_in_rate(db2, torch, binding)
+                    # the box's own pinned host->device copy rate for the same buffer, as the ceiling
+                    stage = torch.empty_like(db2.host_pages, device="cuda")
+                    best = None
+                    for _ in range(3):
+                        torch.cuda.synchronize()
+                        t0 = time.perf_counter()
+                        stage.copy_(db2.host_pages, non_blocking=True)
+                        torch.cuda.synchronize()
+                        dt = time.perf_counter() - t0
+                        best = dt if best is None else min(best, dt)
+                    del stage
                     extra[name].update({"swap_in_GBps": gbs, "swap_in_bytes": int(b2.host_pages.nbytes),
-                                        "swap_in_ms": secs * 1e3})
+                                        "swap_in_ms": secs * 1e3,
+                                        "pinned_h2d_memcpy_GBps": b2.host_pages.nbytes / best / 1e9})
                 del db2, b2
                 torch.cuda.empty_cache()
             except Exception as e:                      # the headline line must still print
