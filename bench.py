@@ -3,8 +3,9 @@
 
 A step = one pass of the hot path over one synthetic batch, inputs resident in HBM:
 prefix-reuse prefill attention on the main stream, the paged KV append of the same
-suffix on a side stream (overlapped, joined at the end of the step) and, for the
-mixed hit/miss workload, the host->pool page swap-in that must land first.
+suffix on a side stream (the two touch disjoint memory and overlap; the streams are
+joined before the clock stops) and, for the mixed hit/miss workload, the host->pool
+page swap-in that must land first.
 Prints ONE JSON line on stdout.
 """
 import argparse
@@ -52,8 +53,8 @@ class Step:
         self.main = torch.cuda.current_stream()
         self.side = torch.cuda.Stream()
         self.mainp, self.sidep = vp(self.main.cuda_stream), vp(self.side.cuda_stream)
-        self.join = torch.cuda.Event()
-        self.fork = torch.cuda.Event()
+        self.join_ev = torch.cuda.Event()
+        self.side.wait_stream(self.main)          # inputs were produced on the main stream
 
     def attention(self):
         rc = self.lib.pbkv_prefix_prefill(self.shape, *self.args_prefill, self.plp, self.nlp, self.outp, self.mainp)
@@ -65,16 +66,21 @@ class Step:
         assert rc == 0, self.lib.pbkv_last_error()
 
     def run(self, ev0=None, ev1=None):
-        self.fork.record(self.main)
-        self.side.wait_event(self.fork)
+        """One step: the append of this batch's suffix is enqueued on the side stream and the
+        attention on the main stream.  The two touch disjoint memory (attention reads the
+        suffix from k_new / v_new, the append writes pool slots no attention reads), so
+        neither stream waits for the other inside a step; the caller joins them before it
+        stops the clock."""
         self.append()
         if ev0 is not None:
             ev0.record(self.main)
         self.attention()
         if ev1 is not None:
             ev1.record(self.main)
-        self.join.record(self.side)
-        self.main.wait_event(self.join)
+
+    def join(self):
+        self.join_ev.record(self.side)
+        self.main.wait_event(self.join_ev)
 
 
 def time_config(name, steps, warmup, torch, binding, W, DeviceBatch):
@@ -85,12 +91,14 @@ def time_config(name, steps, warmup, torch, binding, W, DeviceBatch):
     st = Step(db, torch, binding)
     for _ in range(warmup):
         st.run()
+    st.join()
     torch.cuda.synchronize()
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(steps):
         st.run(*evs[k])
+    st.join()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     kern_ms = float(np.mean([a.elapsed_time(c) for a, c in evs]))
@@ -161,7 +169,7 @@ def main():
         "config": {"workload": b.name, "batch": b.B, "new_tokens": b.N,
                    "prefix_lens": [int(b.prefix_lens.min()), int(b.prefix_lens.max())],
                    "heads_q_kv": [b.Hq, b.Hkv], "head_dim": b.d, "page_size": b.P,
-                   "step": "attention (main stream) + paged append (side stream), one layer"},
+                   "step": "attention (main stream) + paged append (side stream, overlapped), one layer"},
         "tflops_step": flops / (ms_per_step * 1e-3) / 1e12,
         "mfma_util_step": flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": tflops_kernel,

@@ -339,6 +339,200 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0): the loads have landed in LDS
     __syncthreads();
+    if constexpr (QB == 2) {
+    // ---- 32-key pipeline for the 64-column wave ------------------------------------------------
+    // With 64 query columns per wave a 64-key score block is 64 registers, twice over for the
+    // ping-pong; pipelining 32 keys at a time halves that, so the score pipeline, the Q
+    // operands and the LDS operand windows fit the vector half of the register file while
+    // the 128 output accumulators stay in the accumulation half.  Per 64-key tile there
+    // are two sub-steps and two barriers: the second half of K(j) is consumed in the first
+    // sub-step, after which its buffer is refilled with K(j+2).
+    constexpr int NS2 = Gm::DC;                          // steps per phase (DC = 2*DB)
+    constexpr int SPS2 = QB * 16 / NS2;                  // scores per lane per step
+    static_assert(SPS2 % 2 == 0, "scores are converted in pairs");
+    constexpr int WAIT_OLDER = 0x0F70 | (Gm::NI & 15);   // vmcnt(NI): all but the newest tile load have landed
+    static_assert(Gm::NI < 16, "vmcnt immediate");
+    f32x16 Ta[QB], Tb[QB];
+    auto needs_mask_blk = [&](int t, int kb) {
+        return t < TP ? t * BN + 32 * kb + 32 > td.prefix_len : (t - TP) * BN + 32 * kb + 31 > wave_min_tok;
+    };
+    auto mask_blk = [&](f32x16 (&S)[QB], int t, int kb) {
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++) {
+            const int lim = t < TP ? td.prefix_len - 1 - t * BN : my_tokc[qb] - (t - TP) * BN;
+            const int rel = lim - 4 * lh - 32 * kb;
+#pragma unroll
+            for (int r = 0; r < 16; r++)
+                if (8 * (r >> 2) + (r & 3) > rel) S[qb][r] = -INFINITY;
+        }
+    };
+#pragma unroll
+    for (int qb = 0; qb < QB; qb++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) { Ta[qb][r] = 0.f; Tb[qb][r] = 0.f; }
+#pragma unroll
+    for (int dc = 0; dc < Gm::DC; dc++) {
+        const bf16x8 a = k_operand(sK0, dc);
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++)
+            Ta[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][dc], Ta[qb], 0, 0, 0);
+    }
+    if (needs_mask_blk(0, 0)) mask_blk(Ta, 0, 0);
+#pragma unroll
+    for (int qb = 0; qb < QB; qb++) {
+        float mx0 = Ta[qb][0];                            // key 0 is visible to every row: finite
+#pragma unroll
+        for (int r = 1; r < 16; r++) mx0 = fmaxf(mx0, Ta[qb][r]);
+        M[qb] = xmax32(mx0) * c;
+#pragma unroll
+        for (int r = 0; r < 16; r++) Ta[qb][r] = fmaf(Ta[qb][r], c, -M[qb]);
+    }
+    // one sub-step: Tc = pending t of a 32-key block; Tn receives the next block's scores
+    // (block kbn of the tile in ksrc, tile index tn); the PV product uses block kbv of vsrc
+    auto sub = [&](f32x16 (&Tc)[QB], f32x16 (&Tn)[QB], const char *ksrc, int kbn, int tn, const char *vsrc,
+                   int kbv, auto &&issue_loads) __attribute__((always_inline)) {
+#pragma unroll
+        for (int db = 0; db < Gm::DB; db++)
+#pragma unroll
+            for (int qb = 0; qb < QB; qb++) PIN_A(O[db][qb]);
+        bool need = false;
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++) need |= tmax[qb] > RESCALE_LOG2;
+        if (__any(need)) {
+#pragma unroll
+            for (int qb = 0; qb < QB; qb++) {
+                const float d = fmaxf(tmax[qb], 0.f);      // never lower the reference
+                const float alpha = __builtin_amdgcn_exp2f(-d);
+                M[qb] += d;
+                l_part[qb] *= alpha;
+#pragma unroll
+                for (int db = 0; db < Gm::DB; db++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) O[db][qb][r] *= alpha;
+#pragma unroll
+                for (int r = 0; r < 16; r++) Tc[qb][r] -= d;
+            }
+        }
+        float ls[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++) ls[qb] = 0.f;
+        bf16x8 P[QB][2];
+        __builtin_amdgcn_sched_barrier(0);
+#ifndef ABL_NOLOAD
+        issue_loads();
+#endif
+        __builtin_amdgcn_sched_barrier(0);
+        // phase A: next block's S^T on the MFMA beside exp2 / row sum / bf16 pack of this block
+        bf16x8 kop[PF + 1];
+#pragma unroll
+        for (int s = 0; s < PF; s++) kop[s] = k_operand(ksrc, kbn * Gm::DC + s);
+#pragma unroll
+        for (int s = 0; s < NS2; s++) {
+            if (s + PF < NS2) kop[(s + PF) % (PF + 1)] = k_operand(ksrc, kbn * Gm::DC + s + PF);
+#pragma unroll
+            for (int qb = 0; qb < QB; qb++) {
+                if (s == 0) {
+                    f32x16 z;
+#pragma unroll
+                    for (int r = 0; r < 16; r++) z[r] = 0.f;
+                    Tn[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[s % (PF + 1)], qreg[qb][s], z, 0, 0, 0);
+                } else {
+                    Tn[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[s % (PF + 1)], qreg[qb][s], Tn[qb], 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < SPS2; t += 2) {
+                const int idx = s * SPS2 + t, qb = idx / 16, r = idx % 16;
+                f32x2 pv;
+                pv[0] = __builtin_amdgcn_exp2f(Tc[qb][r]);
+                pv[1] = __builtin_amdgcn_exp2f(Tc[qb][r + 1]);
+                ls[qb] += pv[0];
+                ls[qb] += pv[1];
+                const bf16x2 pk = __builtin_convertvector(pv, bf16x2);
+                P[qb][r / 8][r % 8] = pk[0];
+                P[qb][r / 8][r % 8 + 1] = pk[1];
+            }
+        }
+        __builtin_amdgcn_sched_group_barrier(SG_DSRD, PF, 0);
+#pragma unroll
+        for (int s = 0; s < NS2; s++) {
+#pragma unroll
+            for (int qb = 0; qb < QB; qb++) {
+                __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(SG_VALU, (5 * SPS2) / (2 * QB), 0);
+            }
+            if (s + PF < NS2) __builtin_amdgcn_sched_group_barrier(SG_DSRD, 1, 0);
+        }
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++) {
+            PIN_V(P[qb][0]);
+            PIN_V(P[qb][1]);
+            PIN_V(ls[qb]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++) l_part[qb] += ls[qb];
+        // phase B: O += V^T P on the MFMA beside t = S c - M and its row max for the next block
+        if (needs_mask_blk(tn, kbn)) mask_blk(Tn, tn, kbn);
+        __builtin_amdgcn_sched_barrier(0);
+        float mx[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++) mx[qb] = -INFINITY;
+        bf16x8 vop[PF + 1];
+#pragma unroll
+        for (int s = 0; s < PF; s++) vop[s] = v_operand(vsrc, kbv * 2 * Gm::DB + s);
+#pragma unroll
+        for (int s = 0; s < NS2; s++) {
+            if (s + PF < NS2) vop[(s + PF) % (PF + 1)] = v_operand(vsrc, kbv * 2 * Gm::DB + s + PF);
+            const int u = s / Gm::DB, db = s % Gm::DB;
+#pragma unroll
+            for (int qb = 0; qb < QB; qb++)
+                O[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[s % (PF + 1)], P[qb][u], O[db][qb], 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < SPS2; t++) {
+                const int idx = s * SPS2 + t, qb = idx / 16, r = idx % 16;
+                const float tv = fmaf(Tn[qb][r], c, -M[qb]);
+                Tn[qb][r] = tv;
+                mx[qb] = fmaxf(mx[qb], tv);
+            }
+        }
+        __builtin_amdgcn_sched_group_barrier(SG_DSRD, 2 * PF, 1);
+#pragma unroll
+        for (int s = 0; s < NS2; s++) {
+#pragma unroll
+            for (int qb = 0; qb < QB; qb++) {
+                __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 1);
+                __builtin_amdgcn_sched_group_barrier(SG_VALU, (3 * SPS2) / (2 * QB), 1);
+            }
+            if (s + PF < NS2) __builtin_amdgcn_sched_group_barrier(SG_DSRD, 2, 1);
+        }
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++) {
+            PIN_V(mx[qb]);
+            PIN_V(Tn[qb]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int qb = 0; qb < QB; qb++) tmax[qb] = xmax32(mx[qb]);
+    };
+    auto tile_iter = [&](int j, char *kcur, char *knext, char *vcur, char *vnext) __attribute__((always_inline)) {
+        const PageIds pid3 = fetch_page_ids(j + 3);
+        // keys 0-31 of tile j are pending in Ta; S(j, keys 32-63) comes from kcur
+        sub(Ta, Tb, kcur, 1, j, vcur, 0, [&] { load_tile(j + 1, pid1, vnext, vn, true); });
+        __builtin_amdgcn_s_waitcnt(WAIT_OLDER);          // K(j+1) has landed; V(j+1) may be in flight
+        __syncthreads();                                  // ... and every wave is done with kcur
+        sub(Tb, Ta, knext, 0, j + 1, vcur, 1, [&] { load_tile(j + 2, pid2, kcur, kn, false); });
+        __builtin_amdgcn_s_waitcnt(WAIT_OLDER);          // V(j+1) has landed; K(j+2) may be in flight
+        __syncthreads();
+        pid1 = pid2;
+        pid2 = pid3;
+    };
+    for (int j = 0; j < n_tiles; j += 2) {
+        tile_iter(j, sK0, sK1, sV0, sV1);
+        if (j + 1 < n_tiles) tile_iter(j + 1, sK1, sK0, sV1, sV0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                   // nothing may still be writing LDS at exit
+    } else {
     f32x16 Sa[KB][QB], Sb[KB][QB];
 #pragma unroll
     for (int kb = 0; kb < KB; kb++)
@@ -547,6 +741,7 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
         body(j, Sa, Sb, sK1, sV0, sK0, sV1);
         if (j + 1 < n_tiles) body(j + 1, Sb, Sa, sK0, sV1, sK1, sV0);
     }
+    }   // 64-key pipeline
 
 #ifdef PBKV_TRACE
     if (p.trace && l == 0 && w == 0 && blockIdx.x < 4096) {
