@@ -52,7 +52,10 @@ typedef __attribute__((address_space(3))) void lds_void;
 
 constexpr int BN = 64;   // keys per LDS tile (two 32-key MFMA row blocks)
 constexpr int KB = BN / 32;
-constexpr int PF = 3;    // LDS operand prefetch distance, in pipeline steps
+#ifndef PBKV_PF
+#define PBKV_PF 3
+#endif
+constexpr int PF = PBKV_PF;    // LDS operand prefetch distance, in pipeline steps
 constexpr float RESCALE_LOG2 = 8.0f;   // the reference maximum may lag by this much (log2)
 
 template <int D, int NW>
@@ -82,14 +85,14 @@ static __device__ __forceinline__ float xsum32(float x) {
 }
 
 // Launch shape, "QN": Q = 32-row query blocks per wave, N = waves per work-group.
-//   14: 4 waves x 32 rows, two work-groups per CU (default)
-//   18: 8 waves x 32 rows, two waves per SIMD share one set of K/V tiles
+//   14: 4 waves x 32 rows, two work-groups per CU
+//   18: 8 waves x 32 rows, two waves per SIMD share one set of K/V tiles (default)
 //   24: 4 waves x 64 rows, one wave per SIMD
 static int launch_shape() {
     static int v = [] {
         const char *e = getenv("PBKV_ATTN_SHAPE");
-        const int x = e ? atoi(e) : 14;
-        return (x == 18 || x == 24) ? x : 14;
+        const int x = e ? atoi(e) : 18;
+        return (x == 14 || x == 24) ? x : 18;
     }();
     return v;
 }
@@ -237,34 +240,31 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
             if (w / GPP == r) pg = pid.v[(i * RUN + r) % (BN / 16)];
         return pg;
     };
-    auto load_tile = [&](int t, const PageIds &pid, char *buf, const __bf16 *fresh, bool is_v) {
+    // pass i (0..NI-1) of the gather of tile t into buf: this wave's row group i*NW + w
+    auto load_group = [&](int t, const PageIds &pid, char *buf, const __bf16 *fresh, bool is_v, int i) {
+        lds_void *dst = (lds_void *)(buf + (i * NW + w) * 1024);
         if (t < TP) {
-            // rows of logical pages 4t .. 4t+3, valid up to the prefix end
-#pragma unroll
-            for (int i = 0; i < Gm::NI; i++) {
-                const int lp = t * (BN / 16) + (i * RUN) % (BN / 16) + (w / GPP) % RUN;
-                const int prows = max(td.prefix_len - lp * 16, 0);     // >= 16: the whole page (no lane reaches further)
-                const char *pbase = (is_v ? pool_v : pool_k) + (int64_t)group_page(pid, i) * page_bytes;
-                const auto rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)pbase, 0, prows * Gm::ROWB, RSRC_FLAGS);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(buf + (i * NW + w) * 1024), 16,
-                                                         is_v ? voff_pv : voff_pk, 0, 0, 0);
-            }
-            asm volatile("; tile from prefix pages");   // distinct block ends keep the two paths' loads apart
+            // rows of one of the logical pages 4t .. 4t+3, valid up to the prefix end
+            const int lp = t * (BN / 16) + (i * RUN) % (BN / 16) + (w / GPP) % RUN;
+            const int prows = max(td.prefix_len - lp * 16, 0);     // >= 16: the whole page (no lane reaches further)
+            const char *pbase = (is_v ? pool_v : pool_k) + (int64_t)group_page(pid, i) * page_bytes;
+            const auto rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)pbase, 0, prows * Gm::ROWB, RSRC_FLAGS);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst, 16, is_v ? voff_pv : voff_pk, 0, 0, 0);
+            asm volatile("; rows from a prefix page");   // distinct block ends keep the two paths' loads apart
         } else {
-            // RPI suffix tokens per row group, valid up to the last visible token
-            const int sb = (t - TP) * BN + w * Gm::RPI;    // this wave's first token in pass 0
-            const char *sbase = (const char *)fresh + ((td.row0 + sb) * p.Hkv + kvh) * (int64_t)Gm::ROWB;
-#pragma unroll
-            for (int i = 0; i < Gm::NI; i++) {
-                const int srows = max(tok_end - (sb + i * NW * Gm::RPI), 0);   // >= RPI: the whole group
-                const int sbytes = srows > 0 ? (srows - 1) * row_pitch + Gm::ROWB : 0;
-                const auto rsrc = __builtin_amdgcn_make_buffer_rsrc(
-                    (void *)(sbase + (int64_t)i * NW * Gm::RPI * row_pitch), 0, sbytes, RSRC_FLAGS);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(buf + (i * NW + w) * 1024), 16,
-                                                         is_v ? voff_sv : voff_sk, 0, 0, 0);
-            }
-            asm volatile("; tile from the suffix");
+            // RPI suffix tokens, valid up to the last visible token
+            const int s0 = (t - TP) * BN + (i * NW + w) * Gm::RPI;
+            const int srows = max(tok_end - s0, 0);                // >= RPI: the whole group
+            const int sbytes = srows > 0 ? (srows - 1) * row_pitch + Gm::ROWB : 0;
+            const char *sbase = (const char *)fresh + ((td.row0 + s0) * p.Hkv + kvh) * (int64_t)Gm::ROWB;
+            const auto rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)sbase, 0, sbytes, RSRC_FLAGS);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst, 16, is_v ? voff_sv : voff_sk, 0, 0, 0);
+            asm volatile("; rows from the suffix");
         }
+    };
+    auto load_tile = [&](int t, const PageIds &pid, char *buf, const __bf16 *fresh, bool is_v) {
+#pragma unroll
+        for (int i = 0; i < Gm::NI; i++) load_group(t, pid, buf, fresh, is_v, i);
     };
 
     // ---- running state --------------------------------------------------------------------
@@ -339,6 +339,14 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0): the loads have landed in LDS
     __syncthreads();
+#ifdef PBKV_TRACE
+    unsigned long long tr_acc[6] = {0, 0, 0, 0, 0, 0};
+    unsigned long long tr_last = __builtin_amdgcn_s_memtime();
+    const unsigned long long tr_t0 = tr_last, tr_r0 = __builtin_amdgcn_s_memrealtime();
+#define TRACE_MARK(k) do { unsigned long long now_ = __builtin_amdgcn_s_memtime(); tr_acc[k] += now_ - tr_last; tr_last = now_; } while (0)
+#else
+#define TRACE_MARK(k) do {} while (0)
+#endif
     if constexpr (QB == 2) {
     // ---- 32-key pipeline for the 64-column wave ------------------------------------------------
     // With 64 query columns per wave a 64-key score block is 64 registers, twice over for the
@@ -395,6 +403,7 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
         for (int db = 0; db < Gm::DB; db++)
 #pragma unroll
             for (int qb = 0; qb < QB; qb++) PIN_A(O[db][qb]);
+        TRACE_MARK(5);
         bool need = false;
 #pragma unroll
         for (int qb = 0; qb < QB; qb++) need |= tmax[qb] > RESCALE_LOG2;
@@ -421,6 +430,8 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
 #ifndef ABL_NOLOAD
         issue_loads();
 #endif
+        __builtin_amdgcn_sched_barrier(0);
+        TRACE_MARK(0);
         __builtin_amdgcn_sched_barrier(0);
         // phase A: next block's S^T on the MFMA beside exp2 / row sum / bf16 pack of this block
         bf16x8 kop[PF + 1];
@@ -470,10 +481,13 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
             PIN_V(ls[qb]);
         }
         __builtin_amdgcn_sched_barrier(0);
+        TRACE_MARK(1);
 #pragma unroll
         for (int qb = 0; qb < QB; qb++) l_part[qb] += ls[qb];
         // phase B: O += V^T P on the MFMA beside t = S c - M and its row max for the next block
         if (needs_mask_blk(tn, kbn)) mask_blk(Tn, tn, kbn);
+        __builtin_amdgcn_sched_barrier(0);
+        TRACE_MARK(2);
         __builtin_amdgcn_sched_barrier(0);
         float mx[QB];
 #pragma unroll
@@ -512,6 +526,7 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
             PIN_V(Tn[qb]);
         }
         __builtin_amdgcn_sched_barrier(0);
+        TRACE_MARK(3);
 #pragma unroll
         for (int qb = 0; qb < QB; qb++) tmax[qb] = xmax32(mx[qb]);
     };
@@ -521,9 +536,11 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
         sub(Ta, Tb, kcur, 1, j, vcur, 0, [&] { load_tile(j + 1, pid1, vnext, vn, true); });
         __builtin_amdgcn_s_waitcnt(WAIT_OLDER);          // K(j+1) has landed; V(j+1) may be in flight
         __syncthreads();                                  // ... and every wave is done with kcur
+        TRACE_MARK(4);
         sub(Tb, Ta, knext, 0, j + 1, vcur, 1, [&] { load_tile(j + 2, pid2, kcur, kn, false); });
         __builtin_amdgcn_s_waitcnt(WAIT_OLDER);          // V(j+1) has landed; K(j+2) may be in flight
         __syncthreads();
+        TRACE_MARK(4);
         pid1 = pid2;
         pid2 = pid3;
     };
@@ -563,14 +580,6 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
             for (int r = 0; r < 16; r++) Sa[kb][qb][r] = fmaf(Sa[kb][qb][r], c, -M[qb]);
     }
 
-#ifdef PBKV_TRACE
-    unsigned long long tr_acc[6] = {0, 0, 0, 0, 0, 0};
-    unsigned long long tr_last = __builtin_amdgcn_s_memtime();
-    const unsigned long long tr_t0 = tr_last, tr_r0 = __builtin_amdgcn_s_memrealtime();
-#define TRACE_MARK(k) do { unsigned long long now_ = __builtin_amdgcn_s_memtime(); tr_acc[k] += now_ - tr_last; tr_last = now_; } while (0)
-#else
-#define TRACE_MARK(k) do {} while (0)
-#endif
     // ---- one pipelined iteration: tile j; Tc = t(j) ready; Tn receives S(j+1), then t(j+1) ----
     auto body = [&](int j, f32x16 (&Tc)[KB][QB], f32x16 (&Tn)[KB][QB], char *kread, char *vread,
                     char *kwrite, char *vwrite) __attribute__((always_inline)) {
@@ -604,20 +613,28 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
         bf16x8 P[QB][KB][2];
 
         // ---- phase A: S(j+1) = K(j+1) Q^T  ||  P = exp2(t(j)), row sums ---------------------------
-        // Two halves, each a scheduling region of its own, each preceded by half of the
-        // gather for the coming tiles (K(j+2), then V(j+1)): the loads are spread over the
-        // iteration instead of queueing behind the CU's 64 B/clk vector-memory port.
+        // The phase is cut into (up to) four scheduling regions, each preceded by one or two
+        // wave-wide loads of the coming tiles (the NI row groups of K(j+2), then those of
+        // V(j+1)).  A burst of loads from every wave of the CU queues behind the 64 B/clk
+        // vector-memory port and stalls the issuing waves; a load every few MFMAs is absorbed
+        // in the background.  (Shorter regions than four steps cost more than they save.)
+        constexpr int LPR = NW == 4 ? Gm::NI : (2 * Gm::NI > 4 ? 2 * Gm::NI / 4 : 1);    // loads in front of each region
+        constexpr int NREG = 2 * Gm::NI / LPR, RS = NS / NREG;
+        static_assert(NS % NREG == 0 && (2 * Gm::NI) % LPR == 0, "regions hold whole steps");
         bf16x8 kop[PF + 1];
 #pragma unroll
-        for (int half = 0; half < 2; half++) {
+        for (int rg = 0; rg < NREG; rg++) {
             __builtin_amdgcn_sched_barrier(0);
 #ifndef ABL_NOLOAD
-            if (half == 0) load_tile(j + 2, pid2, kwrite, kn, false);
-            else load_tile(j + 1, pid1, vwrite, vn, true);
+#pragma unroll
+            for (int q = rg * LPR; q < (rg + 1) * LPR; q++) {
+                if (q < Gm::NI) load_group(j + 2, pid2, kwrite, kn, false, q);
+                else load_group(j + 1, pid1, vwrite, vn, true, q - Gm::NI);
+            }
 #endif
             __builtin_amdgcn_sched_barrier(0);
-            const int s0 = half * (NS / 2), s1 = s0 + NS / 2;
-            if (half == 0) {
+            const int s0 = rg * RS, s1 = s0 + RS;
+            if (rg == 0) {
 #pragma unroll
                 for (int s = 0; s < PF; s++) kop[s] = k_operand(kread, s);
             }
@@ -651,7 +668,7 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
                 }
             }
             // interleave: per MFMA its share of the exp work, one K operand read per step
-            if (half == 0) __builtin_amdgcn_sched_group_barrier(SG_DSRD, PF, 0);
+            if (rg == 0) __builtin_amdgcn_sched_group_barrier(SG_DSRD, PF, 0);
 #pragma unroll
             for (int s = s0; s < s1; s++) {
 #pragma unroll
@@ -661,17 +678,17 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
                 }
                 if (s + PF < NS) __builtin_amdgcn_sched_group_barrier(SG_DSRD, 1, 0);
             }
-            // keep this half's probabilities and prefetched operands in this block (the
-            // probabilities are only consumed in phase B, and the optimiser would otherwise
+            // keep this region's probabilities, row sums and prefetched operands in this block
+            // (the probabilities are only consumed in phase B, and the optimiser would otherwise
             // sink their computation out of the MFMA shadow)
 #pragma unroll
-            for (int idx = s0 * SPS; idx < s1 * SPS; idx += 8) {
+            for (int idx = s0 * SPS; idx < s1 * SPS; idx += 2) {
                 const int qb = idx / 32, kb2 = (idx % 32) / 16, u = (idx % 16) / 8;
-                PIN_V(P[qb][kb2][u]);
+                if (idx % 8 == 0 || idx == s0 * SPS) PIN_V(P[qb][kb2][u]);
             }
 #pragma unroll
             for (int qb = 0; qb < QB; qb++) PIN_V(ls[qb]);
-            if (half == 0) {
+            if (rg + 1 < NREG) {
 #pragma unroll
                 for (int s = 0; s < PF + 1; s++) PIN_V(kop[s]);
             }
@@ -825,9 +842,9 @@ hipError_t launch_attn_bf16(const AttnParams &p0, int head_dim, hipStream_t s) {
     const int G = p.Hq / p.Hkv;
     const int Gw = G < 4 ? G : 4;
     switch (launch_shape()) {
-        case 18: return head_dim == 128 ? launch_one<128, 1, 8>(p, G, Gw, s) : launch_one<64, 1, 8>(p, G, Gw, s);
+        case 14: return head_dim == 128 ? launch_one<128, 1, 4>(p, G, Gw, s) : launch_one<64, 1, 4>(p, G, Gw, s);
         case 24: return head_dim == 128 ? launch_one<128, 2, 4>(p, G, Gw, s) : launch_one<64, 2, 4>(p, G, Gw, s);
-        default: return head_dim == 128 ? launch_one<128, 1, 4>(p, G, Gw, s) : launch_one<64, 1, 4>(p, G, Gw, s);
+        default: return head_dim == 128 ? launch_one<128, 1, 8>(p, G, Gw, s) : launch_one<64, 1, 8>(p, G, Gw, s);
     }
 }
 
