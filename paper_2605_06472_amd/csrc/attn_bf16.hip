@@ -83,7 +83,7 @@ struct Geom {
     static constexpr int NI = RW / RPI;       // loads per wave per tile
     static_assert(RW % RPI == 0 && NI >= 1, "a wave loads whole 1 KiB row groups");
     static_assert(16 % RW == 0, "a wave's rows of a tile lie in one page");
-    static_assert(H % NI == 0 && PF < H, "loads and operand prefetch fit the half iteration");
+    static_assert(H % NI == 0 && PF < 4 * H, "loads and operand prefetch fit the tile step");
     // XOR applied to the chunk index of row `row` (conflict-free ds_read_b128 of 16
     // consecutive rows for K; conflict-free 4-row x 32-byte transposing reads for V)
     static __device__ __forceinline__ int swz_k(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
@@ -131,6 +131,15 @@ int attn_bf16_tile_tokens(int /*head_dim*/, int group) {
 #define SG_MFMA 0x008
 #define SG_VMRD 0x020
 #define SG_DSRD 0x100
+
+// Two waves share a SIMD's issue port, and the arbiter serves the older wave first: its softmax
+// arithmetic would keep the younger wave's MFMAs off the matrix pipe.  Every MFMA is therefore
+// issued at raised wave priority, so that a waiting MFMA of either wave goes before VALU work.
+#ifndef PBKV_NO_MFMA_PRIO
+#define MFMA_PRIO(x) __builtin_amdgcn_s_setprio(x)
+#else
+#define MFMA_PRIO(x) do {} while (0)
+#endif
 
 #ifdef PBKV_TRACE
 #define TRACE_MARK(k) do { unsigned long long now_ = __builtin_amdgcn_s_memtime(); tr_acc[k] += now_ - tr_last; tr_last = now_; } while (0)
@@ -455,7 +464,9 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
             static_for([&](auto sc) {
                 constexpr int s2 = decltype(sc)::value, m = m0 + s2;
                 if constexpr (m + PF < NM) op[(m + PF) % (PF + 1)] = operand(IntC<m + PF>{});
+                MFMA_PRIO(1);
                 Tn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[m % (PF + 1)], qreg[s2], s2 == 0 ? negM : Tn, 0, 0, 0);
+                MFMA_PRIO(0);
 #ifndef ABL_NOLOAD
                 if constexpr (s2 % (H / Gm::NI) == 0) {
                     constexpr int li2 = s2 / (H / Gm::NI);
@@ -502,7 +513,9 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
             static_for([&](auto sc) {
                 constexpr int s2 = decltype(sc)::value, m = m0 + H + s2;
                 if constexpr (m + PF < NM) op[(m + PF) % (PF + 1)] = operand(IntC<m + PF>{});
+                MFMA_PRIO(1);
                 O[s2 % Gm::DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[m % (PF + 1)], Pp[s2 / Gm::DB], O[s2 % Gm::DB], 0, 0, 0);
+                MFMA_PRIO(0);
                 if constexpr (H == 8) {
                     if constexpr (s2 == 0) exp_pair(10);
                     if constexpr (s2 == 1) max4(0);
