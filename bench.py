@@ -119,6 +119,53 @@ def swap_in_rate(db, torch, binding, reps=3):
     return b.host_pages.nbytes / best / 1e9, best
 
 
+def gather_rate(db, torch, binding, reps=5):
+    """The page gather alone (pbkv_gather_probe: the attention kernel's work units, block-table
+    walk and loads into LDS, no arithmetic).  Staged bytes = what the units pull into LDS
+    (shared pages counted once per unit); distinct bytes = what must come from HBM at least
+    once.  Warm = best of reps back to back; cold = after a 512 MiB fill that evicts L2 / MALL."""
+    b = db.b
+    n_units, T = binding.gather_probe(db.shape, db.k_new, db.v_new, db.kv_pool, db.block_table,
+                                      b.prefix_lens, b.new_lens, None)
+    buf = torch.zeros(n_units, dtype=torch.int32, device="cuda")
+    row_bytes = 2 * b.d * b.elt                                   # K and V of one token, one head
+    G = b.Hq // b.Hkv
+    nsplit = G // min(G, 4)
+    staged = 0
+    for r in range(b.B):
+        p, n = int(b.prefix_lens[r]), int(b.new_lens[r])
+        for t0 in range(0, n, T):
+            staged += (p + min(t0 + T, n)) * row_bytes * b.Hkv * nsplit
+    pages = set()
+    for r in range(b.B):
+        pages.update(int(x) for x in b.block_table[r, :-(-int(b.prefix_lens[r]) // b.P)])
+    distinct = len(pages) * b.page_bytes + b.N * row_bytes * b.Hkv
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def once():
+        e0.record()
+        binding.gather_probe(db.shape, db.k_new, db.v_new, db.kv_pool, db.block_table,
+                             b.prefix_lens, b.new_lens, buf)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3
+    once()
+    warm = min(once() for _ in range(reps))
+    flush = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+    cold = None
+    for _ in range(3):
+        flush.fill_(1)
+        torch.cuda.synchronize()
+        dt = once()
+        cold = dt if cold is None else min(cold, dt)
+    del flush
+    return {"gather_units": n_units, "gather_staged_bytes": staged, "gather_distinct_bytes": distinct,
+            "gather_warm_ms": warm * 1e3, "gather_cold_ms": cold * 1e3,
+            "gather_staged_GBps_warm": staged / warm / 1e9, "gather_staged_GBps_cold": staged / cold / 1e9,
+            "gather_distinct_GBps_cold": distinct / cold / 1e9,
+            "gather_distinct_frac_of_hbm_peak_cold": distinct / cold / 1e9 / PEAK_HBM_GBS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -210,6 +257,8 @@ def main():
                                "new_tokens_per_s": b2.N / (wall2 / steps),
                                "attn_kernel_ms": k2, "attn_tflops": f2 / (k2 * 1e-3) / 1e12,
                                "attn_frac_of_bf16_peak": f2 / (k2 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+                if name == "cfg3":
+                    extra[name].update(gather_rate(db2, torch, binding))
                 if b2.host_pages is not None:
                     gbs, secs = swap_in_rate(db2, torch, binding)
                     # the box's own pinned host->device copy rate for the same buffer, as the ceiling

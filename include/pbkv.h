@@ -130,6 +130,28 @@ int pbkv_swap_in_pages(const pbkv_shape *shape, const void *host_pages,
                        const int32_t *page_ids, int32_t n_pages, void *kv_pool,
                        void *stream);
 
+/*
+ * Gather diagnostic (measurement aid, not a step of the method): runs the page gather of
+ * pbkv_prefix_prefill on bf16 inputs -- the same work units, the same walk through
+ * block_table, the same loads of K/V rows into on-chip memory -- without the arithmetic,
+ * and XORs the 32-bit words of every K and V row a unit stages.  A unit is (block of
+ * *unit_tokens suffix tokens of one request, group of <= 4 query heads of one KV head, KV
+ * head); units are numbered in that nesting order, requests and token blocks ascending.
+ * Unit u covering suffix tokens [t0, t1) of request r and KV head g stages K and V of
+ * prefix tokens [0, p_r) and suffix tokens [0, t1) of head g; unit_xor[u] is the XOR of
+ * all their words.
+ *   k_new, v_new, kv_pool, block_table : device, read only
+ *   prefix_lens, new_lens              : host int32 [batch]
+ *   unit_xor                           : device uint32 [unit_capacity], first *n_units written
+ *   n_units, unit_tokens               : host, written (also when unit_xor is too small:
+ *                                        PBKV_ERR_RANGE, nothing enqueued)
+ * unit_xor == NULL with unit_capacity == 0 only asks for *n_units and *unit_tokens.
+ */
+int pbkv_gather_probe(const pbkv_shape *shape, const void *k_new, const void *v_new,
+                      const void *kv_pool, const int32_t *block_table,
+                      const int32_t *prefix_lens, const int32_t *new_lens, uint32_t *unit_xor,
+                      int64_t unit_capacity, int64_t *n_units, int32_t *unit_tokens, void *stream);
+
 /* Thread-local, library-owned description of the last error on this thread ("" if none). */
 const char *pbkv_last_error(void);
 

@@ -50,6 +50,9 @@ def load():
         lib.pbkv_append_kv.argtypes = [sp, vp, vp, vp, i32p, i32p, i32p, vp]
         lib.pbkv_swap_in_pages.restype = ctypes.c_int
         lib.pbkv_swap_in_pages.argtypes = [sp, vp, i32p, ctypes.c_int32, vp, vp]
+        lib.pbkv_gather_probe.restype = ctypes.c_int
+        lib.pbkv_gather_probe.argtypes = [sp, vp, vp, vp, i32p, i32p, i32p, vp, ctypes.c_int64,
+                                          ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32), vp]
         lib.pbkv_page_bytes.restype = ctypes.c_int64
         lib.pbkv_page_bytes.argtypes = [sp]
         lib.pbkv_last_error.restype = ctypes.c_char_p
@@ -122,3 +125,18 @@ def swap_in_pages(shape, host_pages, page_ids, kv_pool, stream=None):
     ids, idp = _host_i32(page_ids)
     _check(load().pbkv_swap_in_pages(ctypes.byref(shape), _ptr(host_pages), idp,
                                      int(ids.shape[0]), _ptr(kv_pool), _stream(stream)))
+
+
+def gather_probe(shape, k_new, v_new, kv_pool, block_table, prefix_lens, new_lens, unit_xor=None,
+                 stream=None):
+    """Returns (n_units, unit_tokens).  ``unit_xor`` is a device 32-bit integer tensor that
+    receives one word per unit; None only asks for the two numbers."""
+    pl, plp = _host_i32(prefix_lens)
+    nl, nlp = _host_i32(new_lens)
+    n_units, unit_tokens = ctypes.c_int64(0), ctypes.c_int32(0)
+    cap = 0 if unit_xor is None else int(unit_xor.numel())
+    _check(load().pbkv_gather_probe(ctypes.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(kv_pool),
+                                    _ptr(block_table), plp, nlp, _ptr(unit_xor), cap,
+                                    ctypes.byref(n_units), ctypes.byref(unit_tokens),
+                                    None if unit_xor is None else _stream(stream)))
+    return n_units.value, unit_tokens.value

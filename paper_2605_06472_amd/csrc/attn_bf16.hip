@@ -147,7 +147,10 @@ int attn_bf16_tile_tokens(int /*head_dim*/, int group) {
 #define TRACE_MARK(k) do {} while (0)
 #endif
 
-template <int D, int NW>
+// PROBE = true builds the gather diagnostic: the same work units, block-table walk, buffer
+// descriptors, loads into LDS and barriers, but instead of the arithmetic every wave XORs the
+// 32-bit words of the valid rows it finds staged, and the work-group stores one word.
+template <int D, int NW, bool PROBE>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_bf16_kernel(AttnParams p, int G, int Gw) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the body uses gfx950-only builtins and types; the host pass only needs the stub
@@ -359,6 +362,48 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
     unsigned long long tr_last = __builtin_amdgcn_s_memtime();
     const unsigned long long tr_t0 = tr_last, tr_r0 = __builtin_amdgcn_s_memrealtime();
 #endif
+
+    if constexpr (PROBE) {
+        // valid rows of tile t (0 outside the tile range)
+        auto valid_rows = [&](int t) {
+            const int v = t < TP ? td.prefix_len - t * BN : tok_end - (t - TP) * BN;
+            return t < 0 ? 0 : (v < 0 ? 0 : (v > BN ? BN : v));
+        };
+        unsigned acc = 0;
+        auto fold = [&](const char *buf, int rows) {          // the rows this wave loaded
+            const int lrow = l / Gm::CPR;
+#pragma unroll
+            for (int i = 0; i < Gm::NI; i++) {
+                const uint4 v = *(const uint4 *)(buf + (w * Gm::RW + i * Gm::RPI) * ROWB + l * 16);
+                if (w * Gm::RW + i * Gm::RPI + lrow < rows) acc ^= v.x ^ v.y ^ v.z ^ v.w;
+            }
+        };
+        auto pstep = [&](int j, char *kcur, char *knext, char *vprev, char *vcur) __attribute__((always_inline)) {
+            const Src next = tile_src(j + 1);
+            issue_loads(next.k, next.nrec, knext, offs_k(j + 1));
+            issue_loads(prev.v, prev.nrec, vcur, offs_v(j));
+            prev = next;
+            fold(kcur, valid_rows(j));
+            fold(vprev, valid_rows(j - 1));
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+        };
+        for (int j = 0; j <= n_tiles; j += 2) {
+            pstep(j, sK0, sK1, sV1, sV0);
+            if (j + 1 <= n_tiles) pstep(j + 1, sK1, sK0, sV0, sV1);
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) acc ^= __shfl_xor(acc, m, 64);
+        unsigned *red = (unsigned *)sK0;                      // every wave is past its last read of sK0
+        if (l == 0) red[w] = acc;
+        __syncthreads();
+        if (tid == 0) {
+            unsigned x = 0;
+            for (int i = 0; i < NW; i++) x ^= red[i];
+            ((unsigned *)p.out)[((int64_t)td.pad * nsplit + split) * p.Hkv + kvh] = x;
+        }
+        return;
+    } else {
 
     // pending t of the even / odd blocks, and their probabilities (B operands of PV: [u] = keys 16u..16u+15)
     f32x16 T0, T1;
@@ -592,13 +637,14 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
                 *(bf16x4 *)(op + 16 * db + 8 * (b4 & 1) + (D / 2) * (b4 >> 1)) = v;
             }
     }
+    }   // !PROBE
 #endif
 }
 
-template <int D, int NW>
+template <int D, int NW, bool PROBE>
 static hipError_t launch_one(const AttnParams &p, int G, int Gw, hipStream_t s) {
     const unsigned grid = (unsigned)p.n_tiles * (G / Gw) * p.Hkv;
-    hipLaunchKernelGGL((attn_bf16_kernel<D, NW>), dim3(grid), dim3(64 * NW), 0, s, p, G, Gw);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, NW, PROBE>), dim3(grid), dim3(64 * NW), 0, s, p, G, Gw);
     return hipGetLastError();
 }
 
@@ -640,8 +686,21 @@ hipError_t launch_attn_bf16(const AttnParams &p0, int head_dim, hipStream_t s) {
     if (p.n_tiles == 0) return hipSuccess;
     const int G = p.Hq / p.Hkv;
     const int Gw = G < 4 ? G : 4;
-    if (launch_waves() == 4) return head_dim == 128 ? launch_one<128, 4>(p, G, Gw, s) : launch_one<64, 4>(p, G, Gw, s);
-    return head_dim == 128 ? launch_one<128, 8>(p, G, Gw, s) : launch_one<64, 8>(p, G, Gw, s);
+    if (launch_waves() == 4) return head_dim == 128 ? launch_one<128, 4, false>(p, G, Gw, s) : launch_one<64, 4, false>(p, G, Gw, s);
+    return head_dim == 128 ? launch_one<128, 8, false>(p, G, Gw, s) : launch_one<64, 8, false>(p, G, Gw, s);
+}
+
+int attn_bf16_units_per_tile(int num_kv_heads, int group) {
+    const int gw = group < 4 ? group : 4;
+    return (group / gw) * num_kv_heads;
+}
+
+hipError_t launch_gather_probe(const AttnParams &p, int head_dim, hipStream_t s) {
+    if (p.n_tiles == 0) return hipSuccess;
+    const int G = p.Hq / p.Hkv;
+    const int Gw = G < 4 ? G : 4;
+    if (launch_waves() == 4) return head_dim == 128 ? launch_one<128, 4, true>(p, G, Gw, s) : launch_one<64, 4, true>(p, G, Gw, s);
+    return head_dim == 128 ? launch_one<128, 8, true>(p, G, Gw, s) : launch_one<64, 8, true>(p, G, Gw, s);
 }
 
 }  // namespace pbkv

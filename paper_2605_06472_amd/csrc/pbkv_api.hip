@@ -176,6 +176,28 @@ int ring_release(const Lease &l, hipStream_t s) {
     return PBKV_OK;
 }
 
+// Work list of the attention kernels: one tile per block of T suffix tokens of a request,
+// longest (most visible keys) first; `pad` keeps the tile's index in request order.
+int build_tiles(const pbkv_shape *s, const int32_t *prefix_lens, const int32_t *new_lens, int T,
+                std::vector<pbkv::TileDesc> *out) {
+    std::vector<pbkv::TileDesc> &tiles = *out;
+    int64_t row0 = 0;
+    for (int r = 0; r < s->batch; r++) {
+        for (int t0 = 0; t0 < new_lens[r]; t0 += T) {
+            const int64_t idx = (int64_t)tiles.size();
+            tiles.push_back(pbkv::TileDesc{r, t0, prefix_lens[r], new_lens[r], row0, idx});
+        }
+        row0 += new_lens[r];
+    }
+    std::stable_sort(tiles.begin(), tiles.end(), [T](const pbkv::TileDesc &a, const pbkv::TileDesc &b) {
+        const int64_t ka = (int64_t)a.prefix_len + std::min(a.tok0 + T, a.new_len);
+        const int64_t kb = (int64_t)b.prefix_len + std::min(b.tok0 + T, b.new_len);
+        return ka > kb;
+    });
+    if (tiles.size() > (size_t)INT32_MAX / 64) return fail(PBKV_ERR_LIMIT, "too many tiles");
+    return PBKV_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -212,19 +234,7 @@ int pbkv_prefix_prefill(const pbkv_shape *s, const void *q, const void *k_new, c
     const int G = s->num_q_heads / s->num_kv_heads;
     const int T = s->dtype == PBKV_BF16 ? pbkv::attn_bf16_tile_tokens(s->head_dim, G) : pbkv::attn_f32_tile_tokens();
     std::vector<pbkv::TileDesc> tiles;
-    int64_t row0 = 0;
-    for (int r = 0; r < s->batch; r++) {
-        for (int t0 = 0; t0 < new_lens[r]; t0 += T)
-            tiles.push_back(pbkv::TileDesc{r, t0, prefix_lens[r], new_lens[r], row0, 0});
-        row0 += new_lens[r];
-    }
-    // longest tiles first: work per tile grows with the number of visible keys
-    std::stable_sort(tiles.begin(), tiles.end(), [T](const pbkv::TileDesc &a, const pbkv::TileDesc &b) {
-        const int64_t ka = (int64_t)a.prefix_len + std::min(a.tok0 + T, a.new_len);
-        const int64_t kb = (int64_t)b.prefix_len + std::min(b.tok0 + T, b.new_len);
-        return ka > kb;
-    });
-    if (tiles.size() > (size_t)INT32_MAX / 64) return fail(PBKV_ERR_LIMIT, "too many tiles");
+    if ((rc = build_tiles(s, prefix_lens, new_lens, T, &tiles))) return rc;
 
     Lease lease;
     if ((rc = ring_acquire(tiles.size() * sizeof(pbkv::TileDesc), &lease))) return rc;
@@ -243,6 +253,59 @@ int pbkv_prefix_prefill(const pbkv_shape *s, const void *q, const void *k_new, c
                                          : pbkv::launch_attn_f32(p, s->head_dim, st);
     int rel = ring_release(lease, st);
     if (e != hipSuccess) return fail_hip(e, "attention launch");
+    return rel;
+}
+
+int pbkv_gather_probe(const pbkv_shape *s, const void *k_new, const void *v_new, const void *kv_pool,
+                      const int32_t *block_table, const int32_t *prefix_lens, const int32_t *new_lens,
+                      uint32_t *unit_xor, int64_t unit_capacity, int64_t *n_units, int32_t *unit_tokens,
+                      void *stream) {
+    g_err[0] = 0;
+    int rc = check_shape(s, true);
+    if (rc) return rc;
+    if (s->dtype != PBKV_BF16) return fail(PBKV_ERR_DTYPE, "pbkv_gather_probe: bf16 only");
+    if (!n_units || !unit_tokens) return fail(PBKV_ERR_NULL, "pbkv_gather_probe: NULL argument");
+    const int G = s->num_q_heads / s->num_kv_heads;
+    const int T = pbkv::attn_bf16_tile_tokens(s->head_dim, G);
+    *unit_tokens = T;
+    *n_units = 0;
+    if (s->batch == 0) return PBKV_OK;
+    if (!k_new || !v_new || !kv_pool || !block_table || !prefix_lens || !new_lens)
+        return fail(PBKV_ERR_NULL, "pbkv_gather_probe: NULL argument");
+    int64_t N = 0;
+    if ((rc = check_lens(s, prefix_lens, new_lens, &N))) return rc;
+    std::vector<pbkv::TileDesc> tiles;
+    if ((rc = build_tiles(s, prefix_lens, new_lens, T, &tiles))) return rc;
+    const int64_t units = (int64_t)tiles.size() * pbkv::attn_bf16_units_per_tile(s->num_kv_heads, G);
+    *n_units = units;
+    if (units == 0 || (!unit_xor && unit_capacity == 0)) return PBKV_OK;   // nothing to do / size query
+    if (!unit_xor) return fail(PBKV_ERR_NULL, "pbkv_gather_probe: NULL unit_xor");
+    if (unit_capacity < units)
+        return fail(PBKV_ERR_RANGE, "pbkv_gather_probe: %lld units need room, unit_xor holds %lld", (long long)units,
+                    (long long)unit_capacity);
+    if ((rc = check_aligned(k_new, "k_new")) || (rc = check_aligned(v_new, "v_new")) ||
+        (rc = check_aligned(kv_pool, "kv_pool")))
+        return rc;
+    if ((rc = check_device_ptr(k_new, "k_new")) || (rc = check_device_ptr(v_new, "v_new")) ||
+        (rc = check_device_ptr(kv_pool, "kv_pool")) || (rc = check_device_ptr(block_table, "block_table")) ||
+        (rc = check_device_ptr(unit_xor, "unit_xor")))
+        return rc;
+
+    Lease lease;
+    if ((rc = ring_acquire(tiles.size() * sizeof(pbkv::TileDesc), &lease))) return rc;
+    memcpy(lease.host, tiles.data(), tiles.size() * sizeof(pbkv::TileDesc));
+    pbkv::AttnParams p;
+    p.q = nullptr; p.k_new = k_new; p.v_new = v_new; p.kv_pool = kv_pool; p.out = unit_xor;
+    p.block_table = block_table;
+    p.tiles = (const pbkv::TileDesc *)lease.dev;
+    p.n_tiles = (int32_t)tiles.size();
+    p.Hq = s->num_q_heads; p.Hkv = s->num_kv_heads;
+    p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
+    p.trace = nullptr;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = pbkv::launch_gather_probe(p, s->head_dim, st);
+    int rel = ring_release(lease, st);
+    if (e != hipSuccess) return fail_hip(e, "gather probe launch");
     return rel;
 }
 

@@ -14,7 +14,7 @@ struct TileDesc {
     int32_t prefix_len;  // p_r
     int32_t new_len;     // n_r
     int64_t row0;        // packed row (into q / k_new / v_new / out) of the request's token 0
-    int64_t pad;
+    int64_t pad;         // index of the tile in request order (before the longest-first sort)
 };
 static_assert(sizeof(TileDesc) == 32, "TileDesc is read as two 16-byte words");
 
@@ -53,6 +53,11 @@ int attn_f32_tile_tokens();
 // Launchers: all arguments already validated.  Return the hipError of the launch.
 hipError_t launch_attn_bf16(const AttnParams &p, int head_dim, hipStream_t s);
 hipError_t launch_attn_f32(const AttnParams &p, int head_dim, hipStream_t s);
+// Gather diagnostic: p.out is a uint32 array with one word per work unit, units ordered
+// (tile in request order, query-head split, KV head); attn_bf16_units_per_tile gives the
+// number of units of one tile.
+hipError_t launch_gather_probe(const AttnParams &p, int head_dim, hipStream_t s);
+int attn_bf16_units_per_tile(int num_kv_heads, int group);
 hipError_t launch_append(const AppendParams &p, int head_dim, int elt_bytes, hipStream_t s);
 hipError_t launch_swap_in(const void *host_pages, const int32_t *page_ids_dev, int32_t n_pages,
                           void *kv_pool, int64_t page_bytes, hipStream_t s);
