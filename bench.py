@@ -119,6 +119,32 @@ def swap_in_rate(db, torch, binding, reps=3):
     return b.host_pages.nbytes / best / 1e9, best
 
 
+def swap_out_rate(db, torch, binding, reps=3):
+    """Pool->host swap-out of the pages the batch swapped in, GB/s (best of reps), and the box's
+    pinned device->host copy rate for a buffer of the same size."""
+    b = db.b
+    host = torch.empty_like(db.host_pages).pin_memory()
+    best = None
+    for _ in range(reps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        binding.swap_out_pages(db.shape, db.kv_pool, b.swap_page_ids, host)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    stage = torch.empty_like(db.host_pages, device="cuda")
+    ceil = None
+    for _ in range(reps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        host.copy_(stage, non_blocking=True)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ceil = dt if ceil is None else min(ceil, dt)
+    return {"swap_out_GBps": host.numel() * host.element_size() / best / 1e9, "swap_out_ms": best * 1e3,
+            "pinned_d2h_memcpy_GBps": host.numel() * host.element_size() / ceil / 1e9}
+
+
 def gather_rate(db, torch, binding, reps=5):
     """The page gather alone (pbkv_gather_probe: the attention kernel's work units, block-table
     walk and loads into LDS, no arithmetic).  Staged bytes = what the units pull into LDS
@@ -275,6 +301,7 @@ def main():
                     extra[name].update({"swap_in_GBps": gbs, "swap_in_bytes": int(b2.host_pages.nbytes),
                                         "swap_in_ms": secs * 1e3,
                                         "pinned_h2d_memcpy_GBps": b2.host_pages.nbytes / best / 1e9})
+                    extra[name].update(swap_out_rate(db2, torch, binding))
                 del db2, b2
                 torch.cuda.empty_cache()
             except Exception as e:                      # the headline line must still print

@@ -131,6 +131,20 @@ int pbkv_swap_in_pages(const pbkv_shape *shape, const void *host_pages,
                        void *stream);
 
 /*
+ * Pool -> host page swap-out (Sec. 2: with HiCache, cache evicted from the GPU is retained
+ * in host memory), the mirror of pbkv_swap_in_pages: host page i := pool page
+ * page_ids[i], whole pages, byte-exact; the pool is not modified.
+ *   kv_pool    : device, read only
+ *   page_ids   : host int32 [n_pages], read during the call; each in [0, num_pages)
+ *                (else PBKV_ERR_RANGE, nothing enqueued); a page may be named more than once
+ *   host_pages : pinned host memory, [n_pages][pbkv_page_bytes], written by the GPU while the
+ *                stream runs; its content is defined once the stream has reached this call
+ * Only shape->num_kv_heads, head_dim, page_size, num_pages and dtype are used.
+ */
+int pbkv_swap_out_pages(const pbkv_shape *shape, const void *kv_pool, const int32_t *page_ids,
+                        int32_t n_pages, void *host_pages, void *stream);
+
+/*
  * Gather diagnostic (measurement aid, not a step of the method): runs the page gather of
  * pbkv_prefix_prefill on bf16 inputs -- the same work units, the same walk through
  * block_table, the same loads of K/V rows into on-chip memory -- without the arithmetic,

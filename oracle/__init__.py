@@ -29,6 +29,8 @@ def _bind(path):
                                            vp, vp, vp, vp, vp, vp]
         lib.pbkv_oracle_swap_in.restype = ctypes.c_int
         lib.pbkv_oracle_swap_in.argtypes = [i64, i64, vp, vp, i64, vp]
+        lib.pbkv_oracle_swap_out.restype = ctypes.c_int
+        lib.pbkv_oracle_swap_out.argtypes = [i64, i64, vp, vp, i64, vp]
         lib.pbkv_oracle_threads.restype = ctypes.c_int
     return lib
 
@@ -137,3 +139,18 @@ def swap_in(host_pages, page_ids, kv_pool):
     if rc != 0:
         raise ValueError("oracle rejected its arguments (code %d)" % rc)
     return pool
+
+
+def swap_out(kv_pool, page_ids):
+    """Return host pages [n][...page shape]: host page i is a copy of pool page page_ids[i]."""
+    pool, pp = _c(kv_pool)
+    num_pages = pool.shape[0]
+    page_bytes = pool[0].nbytes if num_pages else 0
+    page_ids, ip = _c(page_ids, np.int32)
+    n = page_ids.shape[0]
+    host = np.zeros((n,) + pool.shape[1:], pool.dtype)
+    rc = _lib().pbkv_oracle_swap_out(page_bytes, num_pages, pp, ip, n,
+                                     host.ctypes.data_as(ctypes.c_void_p))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments (code %d)" % rc)
+    return host

@@ -226,3 +226,21 @@ int pbkv_oracle_swap_in(int64_t page_bytes, int64_t num_pages,
     }
     return 0;
 }
+
+/*
+ * Pool -> host page swap-out (Sec. 2, HiCache: cache evicted from the GPU is retained in
+ * host memory): host page i becomes a copy of pool page page_ids[i].  Whole pages, byte move;
+ * the pool is only read.
+ */
+int pbkv_oracle_swap_out(int64_t page_bytes, int64_t num_pages,
+                         const void *kv_pool, const int32_t *page_ids,
+                         int64_t n_pages, void *host_pages)
+{
+    for (int64_t i = 0; i < n_pages; i++) {
+        if (page_ids[i] < 0 || page_ids[i] >= num_pages) return -4;
+        memcpy((char *)host_pages + (size_t)i * (size_t)page_bytes,
+               (const char *)kv_pool + (size_t)page_ids[i] * (size_t)page_bytes,
+               (size_t)page_bytes);
+    }
+    return 0;
+}

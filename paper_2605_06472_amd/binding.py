@@ -50,6 +50,8 @@ def load():
         lib.pbkv_append_kv.argtypes = [sp, vp, vp, vp, i32p, i32p, i32p, vp]
         lib.pbkv_swap_in_pages.restype = ctypes.c_int
         lib.pbkv_swap_in_pages.argtypes = [sp, vp, i32p, ctypes.c_int32, vp, vp]
+        lib.pbkv_swap_out_pages.restype = ctypes.c_int
+        lib.pbkv_swap_out_pages.argtypes = [sp, vp, i32p, ctypes.c_int32, vp, vp]
         lib.pbkv_gather_probe.restype = ctypes.c_int
         lib.pbkv_gather_probe.argtypes = [sp, vp, vp, vp, i32p, i32p, i32p, vp, ctypes.c_int64,
                                           ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32), vp]
@@ -125,6 +127,12 @@ def swap_in_pages(shape, host_pages, page_ids, kv_pool, stream=None):
     ids, idp = _host_i32(page_ids)
     _check(load().pbkv_swap_in_pages(ctypes.byref(shape), _ptr(host_pages), idp,
                                      int(ids.shape[0]), _ptr(kv_pool), _stream(stream)))
+
+
+def swap_out_pages(shape, kv_pool, page_ids, host_pages, stream=None):
+    ids, idp = _host_i32(page_ids)
+    _check(load().pbkv_swap_out_pages(ctypes.byref(shape), _ptr(kv_pool), idp, int(ids.shape[0]),
+                                      _ptr(host_pages), _stream(stream)))
 
 
 def gather_probe(shape, k_new, v_new, kv_pool, block_table, prefix_lens, new_lens, unit_xor=None,

@@ -389,4 +389,33 @@ int pbkv_swap_in_pages(const pbkv_shape *s, const void *host_pages, const int32_
     return rel;
 }
 
+int pbkv_swap_out_pages(const pbkv_shape *s, const void *kv_pool, const int32_t *page_ids,
+                        int32_t n_pages, void *host_pages, void *stream) {
+    g_err[0] = 0;
+    int rc = check_shape(s, false);
+    if (rc) return rc;
+    if (n_pages < 0) return fail(PBKV_ERR_RANGE, "n_pages %d", n_pages);
+    if (n_pages == 0) return PBKV_OK;
+    if (!host_pages || !page_ids || !kv_pool) return fail(PBKV_ERR_NULL, "pbkv_swap_out_pages: NULL argument");
+    for (int i = 0; i < n_pages; i++) {
+        const int32_t id = page_ids[i];
+        if (id < 0 || id >= s->num_pages)
+            return fail(PBKV_ERR_RANGE, "page_ids[%d] = %d outside pool of %d pages", i, id, s->num_pages);
+    }
+    if ((rc = check_aligned(host_pages, "host_pages")) || (rc = check_aligned(kv_pool, "kv_pool"))) return rc;
+    const void *host_dev = nullptr;
+    if ((rc = check_pinned_ptr(host_pages, "host_pages", &host_dev))) return rc;
+    if ((rc = check_device_ptr(kv_pool, "kv_pool"))) return rc;
+
+    Lease lease;
+    if ((rc = ring_acquire((size_t)n_pages * sizeof(int32_t), &lease))) return rc;
+    memcpy(lease.host, page_ids, (size_t)n_pages * sizeof(int32_t));
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = pbkv::launch_swap_out(kv_pool, (const int32_t *)lease.dev, n_pages, (void *)host_dev,
+                                         pbkv_page_bytes(s), st);
+    int rel = ring_release(lease, st);
+    if (e != hipSuccess) return fail_hip(e, "swap-out launch");
+    return rel;
+}
+
 }  // extern "C"

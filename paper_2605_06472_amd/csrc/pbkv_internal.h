@@ -62,4 +62,7 @@ hipError_t launch_append(const AppendParams &p, int head_dim, int elt_bytes, hip
 hipError_t launch_swap_in(const void *host_pages, const int32_t *page_ids_dev, int32_t n_pages,
                           void *kv_pool, int64_t page_bytes, hipStream_t s);
 
+hipError_t launch_swap_out(const void *kv_pool, const int32_t *page_ids_dev, int32_t n_pages,
+                           void *host_pages, int64_t page_bytes, hipStream_t s);
+
 }  // namespace pbkv

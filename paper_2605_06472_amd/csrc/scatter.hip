@@ -80,4 +80,41 @@ hipError_t launch_swap_in(const void *host_pages, const int32_t *page_ids_dev, i
     return hipGetLastError();
 }
 
+// Swap-out: the mirror image -- pool page page_ids[i] is copied to host page i, read from HBM
+// and written over the host link through the mapped pointer (posted writes, so the link is
+// kept full without many loads in flight).
+__global__ __launch_bounds__(256) void swap_out_kernel(const u32x4 *__restrict__ pool,
+                                                       const int32_t *__restrict__ page_ids,
+                                                       u32x4 *__restrict__ host_pages, int page_chunks,
+                                                       int wgs_per_page) {
+    const int page = blockIdx.x / wgs_per_page;
+    const int part = blockIdx.x % wgs_per_page;
+    const int64_t src_page = page_ids[page];
+    const u32x4 *src = pool + src_page * page_chunks;
+    u32x4 *dst = host_pages + (int64_t)page * page_chunks;
+    const int base = part * SWAP_CHUNKS + threadIdx.x;
+    u32x4 v[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int c = base + i * 256;
+        if (c < page_chunks) v[i] = src[c];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int c = base + i * 256;
+        if (c < page_chunks) __builtin_nontemporal_store(v[i], dst + c);
+    }
+}
+
+hipError_t launch_swap_out(const void *kv_pool, const int32_t *page_ids_dev, int32_t n_pages,
+                           void *host_pages, int64_t page_bytes, hipStream_t s) {
+    if (n_pages == 0) return hipSuccess;
+    const int page_chunks = (int)(page_bytes / 16);
+    const int wgs_per_page = (page_chunks + SWAP_CHUNKS - 1) / SWAP_CHUNKS;
+    hipLaunchKernelGGL(swap_out_kernel, dim3((unsigned)n_pages * wgs_per_page), dim3(256), 0, s,
+                       (const u32x4 *)kv_pool, page_ids_dev, (u32x4 *)host_pages, page_chunks,
+                       wgs_per_page);
+    return hipGetLastError();
+}
+
 }  // namespace pbkv

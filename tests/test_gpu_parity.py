@@ -257,3 +257,28 @@ def test_pageable_host_memory_is_rejected():
     with pytest.raises(binding.PbkvError) as e:
         binding.swap_in_pages(db.shape, pageable, b.swap_page_ids, db.kv_pool)
     assert e.value.code == -6
+
+
+def test_swap_out_bit_exact_and_round_trip(oracle):
+    """Pool -> pinned host page gather (the host-tier half that swap-in mirrors): equal to the
+    oracle byte for byte, pool untouched, and swapped back into other slots it reproduces the pages."""
+    b = W.ragged_small(41, "bf16", prefix_lens=(48, 100, 7), new_lens=(3, 9, 20))
+    db = DeviceBatch(b)
+    rng = np.random.default_rng(11)
+    ids = rng.permutation(b.num_pages)[:11].astype(np.int32)
+    ids[4] = ids[1]
+    want = oracle.swap_out(b.kv_pool, ids)
+    host = torch.zeros((len(ids),) + tuple(db.kv_pool.shape[1:]), dtype=db.kv_pool.dtype).pin_memory()
+    binding.swap_out_pages(db.shape, db.kv_pool, ids, host)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_numpy(host), want)
+    assert np.array_equal(to_numpy(db.kv_pool), b.kv_pool)
+    dst = np.setdiff1d(np.arange(b.num_pages, dtype=np.int32), ids)[:len(ids)].astype(np.int32)
+    binding.swap_in_pages(db.shape, host, dst, db.kv_pool)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_numpy(db.kv_pool), oracle.swap_in(want, dst, b.kv_pool))
+    with pytest.raises(binding.PbkvError) as e:
+        binding.swap_out_pages(db.shape, db.kv_pool, np.array([b.num_pages], np.int32), host)
+    assert e.value.code == -4
+    # empty list is a no-op
+    binding.swap_out_pages(db.shape, db.kv_pool, np.zeros(0, np.int32), host)

@@ -27,6 +27,8 @@ MUTATIONS = {
     "append_wrong_slot": ("+ pos % P) * rowb;", "+ t % P) * rowb;"),
     "swap_in_wrong_source": ("(const char *)host_pages + (size_t)i * (size_t)page_bytes",
                              "(const char *)host_pages + (size_t)(n_pages - 1 - i) * (size_t)page_bytes"),
+    "swap_out_wrong_page": ("(const char *)kv_pool + (size_t)page_ids[i] * (size_t)page_bytes",
+                            "(const char *)kv_pool + (size_t)i * (size_t)page_bytes"),
 }
 
 
@@ -52,7 +54,10 @@ def _pins_pass(oracle) -> bool:
                            nonresident=(2, 5))
         want = b.kv_pool.copy()
         want[b.swap_page_ids] = b.host_pages
-        return bool(np.array_equal(oracle.swap_in(b.host_pages, b.swap_page_ids, b.kv_pool), want))
+        if not np.array_equal(oracle.swap_in(b.host_pages, b.swap_page_ids, b.kv_pool), want):
+            return False
+        ids = np.array([5, 0, 17, 5], np.int32)
+        return bool(np.array_equal(oracle.swap_out(b.kv_pool, ids), b.kv_pool[ids]))
     except (ValueError, FloatingPointError):
         return False
 

@@ -265,3 +265,22 @@ def test_swap_in_matches_fancy_index(oracle):
     np.testing.assert_allclose(out, ref, atol=1e-12)
     stale = oracle.prefill(b.q, b.k_new, b.v_new, b.kv_pool, b.block_table, b.prefix_lens, b.new_lens)
     assert np.abs(stale - ref).max() > 1e-3
+
+
+def test_swap_out_matches_fancy_index_and_round_trips(oracle):
+    """Swap-out (Sec. 2, host tier) is a page gather: equal to numpy fancy indexing, pool untouched,
+    and swap-out followed by swap-in into other slots reproduces the pages there."""
+    b = W.ragged_small(33, "bf16", Hq=4, Hkv=2, d=64, prefix_lens=(48, 100), new_lens=(3, 9))
+    rng = np.random.default_rng(5)
+    ids = rng.permutation(b.num_pages)[:9].astype(np.int32)
+    ids[3] = ids[0]                                        # a page may be named twice
+    pool0 = b.kv_pool.copy()
+    host = oracle.swap_out(b.kv_pool, ids)
+    assert np.array_equal(b.kv_pool, pool0)
+    assert np.array_equal(host, b.kv_pool[ids])
+    assert not np.array_equal(host[0], host[1])
+    dst = np.setdiff1d(np.arange(b.num_pages, dtype=np.int32), ids)[:9].astype(np.int32)
+    back = oracle.swap_in(host, dst, b.kv_pool)
+    assert np.array_equal(back[dst], b.kv_pool[ids])
+    with pytest.raises(ValueError):
+        oracle.swap_out(b.kv_pool, np.array([b.num_pages], np.int32))
