@@ -145,6 +145,60 @@ def swap_out_rate(db, torch, binding, reps=3):
             "pinned_d2h_memcpy_GBps": host.numel() * host.element_size() / ceil / 1e9}
 
 
+def policy_latency(steps=6000, warm=3000, concurrency=72):
+    """Per-call latency of the policy core (host C++) on the synthetic workflow driver at the
+    paper's operating point of 72 concurrent workflows (App. F, Table of scheduler overhead),
+    with the reference model timed beside it on a shorter run of the same trace."""
+    from paper_2605_06472_amd import policy as PC, policy_sim as SIM
+    from oracle import policy_oracle as PO
+
+    class Timed:
+        def __init__(self, inner):
+            self.inner, self.t = inner, {"forecast": [], "evict": [], "prefetch": []}
+
+        def __getattr__(self, name):
+            f = getattr(self.inner, name)
+            if name not in self.t:
+                return f
+            acc = self.t[name]
+
+            def call(*a, **k):
+                t0 = time.perf_counter_ns()
+                r = f(*a, **k)
+                acc.append(time.perf_counter_ns() - t0)
+                return r
+            return call
+
+    def run(pol, n_warm, n_steps):
+        tp = Timed(pol)
+        w = SIM.World(tp, capacity_pages=900, concurrency=concurrency, seed=5, horizon=3, prefetch=True)
+        w.run(n_warm)
+        for v in tp.t.values():
+            v.clear()
+        w.run(n_steps)
+        nodes_per_wf = np.mean([2 + sum(len(c) for (wf, a), c in w.chains.items() if wf == x) for x in w.cur])
+        return {k: float(np.mean(v)) / 1e3 for k, v in tp.t.items() if v}, float(nodes_per_wf), len(w.tier)
+
+    core, npw, n_nodes = run(PC.Policy(6, 3, 0.7, PC.MODE_HE), warm, steps)
+    p0 = PC.Policy(6, 3, 0.7, PC.MODE_HE)
+    t0 = time.perf_counter_ns()
+    for _ in range(20000):
+        p0.retired_pages()
+    call_us = (time.perf_counter_ns() - t0) / 20000 / 1e3          # cost of one call through ctypes
+    model, _, _ = run(PO.PolicyOracle(6, 3, 0.7, PO.MODE_HE), 300, 300)
+    return {"workload": "synthetic looped call graph, 6 agents, K=3, gamma=0.7, %d concurrent workflows, "
+                        "900-page GPU tier, %d nodes tracked" % (concurrency, n_nodes),
+            "forecast_refresh_us": core["forecast"], "nodes_rescored_per_refresh": npw,
+            "score_update_us_per_node": max(core["forecast"] - call_us, 0.0) / npw,
+            "evict_decision_us": core["evict"], "prefetch_decision_us": core["prefetch"],
+            "ctypes_call_overhead_us": call_us,
+            "reference_model_us": {"forecast_refresh": model["forecast"], "evict_decision": model["evict"],
+                                   "prefetch_decision": model["prefetch"]},
+            "paper_context_us": {"ScoreUpdate": 1.53, "EvictDecision": 440.0, "PrefetchDecision": 640.0,
+                                 "note": "App. F table: Python scheduler hooks inside SGLang on the paper's host, "
+                                         "HoVer+LangChain at concurrency 72; not the same trace"}}
+
+
 def gather_rate(db, torch, binding, reps=5):
     """The page gather alone (pbkv_gather_probe: the attention kernel's work units, block-table
     walk and loads into LDS, no arithmetic).  Staged bytes = what the units pull into LDS
@@ -306,6 +360,10 @@ def main():
                 torch.cuda.empty_cache()
             except Exception as e:                      # the headline line must still print
                 extra[name] = {"error": repr(e)}
+        try:
+            extra["policy"] = policy_latency()
+        except Exception as e:
+            extra["policy"] = {"error": repr(e)}
         line["extra"] = extra
 
     print(json.dumps(line))

@@ -68,7 +68,7 @@ constexpr int BN = 64;   // keys per LDS tile (two 32-key blocks)
 #define PBKV_PF 3
 #endif
 constexpr int PF = PBKV_PF;    // LDS operand prefetch distance, in MFMA steps
-constexpr float RESCALE_LOG2 = 8.0f;   // the reference maximum may lag by this much (log2)
+[[maybe_unused]] constexpr float RESCALE_LOG2 = 8.0f;   // the reference maximum may lag by this much (log2)
 
 template <int D, int NW>
 struct Geom {
@@ -94,11 +94,11 @@ template <int I> struct IntC { static constexpr int value = I; };
 template <class F, int... Is>
 static __device__ __forceinline__ void static_for(F &&f, std::integer_sequence<int, Is...>) { (f(IntC<Is>{}), ...); }
 
-static __device__ __forceinline__ float xmax32(float x) {
+[[maybe_unused]] static __device__ __forceinline__ float xmax32(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
-static __device__ __forceinline__ float xsum32(float x) {
+[[maybe_unused]] static __device__ __forceinline__ float xsum32(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }

@@ -26,6 +26,20 @@ int fail(int code, const char *fmt, ...) {
     return code;
 }
 
+}  // namespace
+
+// error text for the translation units that hold no HIP code (the policy core)
+int pbkv::set_error(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+void pbkv::clear_error() { g_err[0] = 0; }
+
+namespace {
+
 int fail_hip(hipError_t e, const char *what) {
     return fail(PBKV_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
 }

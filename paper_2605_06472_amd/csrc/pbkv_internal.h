@@ -5,6 +5,10 @@
 
 namespace pbkv {
 
+// Sets the thread's last-error text (returned by pbkv_last_error) and hands back `code`.
+int set_error(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
 // One unit of attention work: a block of consecutive suffix tokens of one request.
 // Written by the host into pinned memory and read by the kernel through the mapped
 // pointer (32 bytes, two 16-byte loads).
