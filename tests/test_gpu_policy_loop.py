@@ -1,0 +1,162 @@
+"""Closing the loop on the GPU: the policy core decides, the page movers move, attention reads.
+
+A small two-tier cache (GPU pool + pinned host buffer) holds radix-tree nodes of a few
+workflows.  The policy core's eviction list drives pbkv_swap_out_pages, its prefetch list and
+the hit path drive pbkv_swap_in_pages into OTHER pool slots (freed slots are scribbled over
+first, so the data can only come back from the host tier), and the prefill attention of a
+request over the re-assembled prefix must equal (i) the oracle attention over a numpy mirror
+that was moved by the oracle's own swap-out / swap-in and (ii) the brute force over the
+contiguous node contents, which never sees a page id."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from paper_2605_06472_amd import binding, workloads as W          # noqa: E402
+from paper_2605_06472_amd import policy as PC                      # noqa: E402
+from tests import bruteforce                                        # noqa: E402
+from tests.gpu_util import assert_close, to_numpy, to_torch        # noqa: E402
+
+HQ, HKV, D, P = 8, 2, 128, 16
+NP_GPU, NP_HOST = 24, 48
+
+
+class TwoTier:
+    """Page bookkeeping of the test (which node lives in which pages); no arithmetic of the method."""
+
+    def __init__(self, oracle, seed):
+        self.oracle = oracle
+        self.rng = np.random.default_rng(seed)
+        self.shape = binding.make_shape(1, HQ, HKV, D, P, NP_GPU, 16, "bf16")
+        garbage = W.normal_tensor(seed, 1, (NP_GPU, 2, HKV, P, D), 1.0, "bf16")
+        self.mirror = garbage.copy()                                   # numpy mirror of the pool
+        self.pool = to_torch(garbage)
+        self.host = torch.zeros((NP_HOST, 2, HKV, P, D), dtype=torch.bfloat16).pin_memory()
+        self.host_mirror = np.zeros((NP_HOST, 2, HKV, P, D), np.uint16)
+        self.free_gpu = list(range(NP_GPU))
+        self.rng.shuffle(self.free_gpu)
+        self.free_host = list(range(NP_HOST))
+        self.gpu_pages, self.host_slots, self.kv = {}, {}, {}
+
+    def create(self, nid, pages):
+        k = W.f32_to_bf16_bits(self.rng.standard_normal((pages * P, HKV, D)).astype(np.float32) * 0.7)
+        v = W.f32_to_bf16_bits(self.rng.standard_normal((pages * P, HKV, D)).astype(np.float32) * 0.7)
+        self.kv[nid] = (k, v)
+        ids = [self.free_gpu.pop() for _ in range(pages)]
+        self.gpu_pages[nid] = ids
+        for j, pg in enumerate(ids):
+            self.mirror[pg, 0] = k[j * P:(j + 1) * P].transpose(1, 0, 2)
+            self.mirror[pg, 1] = v[j * P:(j + 1) * P].transpose(1, 0, 2)
+        self.pool.copy_(to_torch(self.mirror))
+
+    def swap_out(self, nodes):
+        """Policy says these nodes leave the GPU: one pbkv_swap_out_pages call, then the slots are reused."""
+        ids, slots = [], []
+        for nid in nodes:
+            s = [self.free_host.pop() for _ in self.gpu_pages[nid]]
+            ids += self.gpu_pages[nid]
+            slots += s
+            self.host_slots[nid] = s
+        n = len(ids)
+        staging = torch.zeros((n, 2, HKV, P, D), dtype=torch.bfloat16).pin_memory()
+        binding.swap_out_pages(self.shape, self.pool, np.array(ids, np.int32), staging)
+        torch.cuda.synchronize()
+        want = self.oracle.swap_out(self.mirror, np.array(ids, np.int32))
+        assert np.array_equal(to_numpy(staging), want)
+        for j, slot in enumerate(slots):
+            self.host[slot].copy_(staging[j])
+            self.host_mirror[slot] = want[j]
+        # the freed slots are scribbled over: the content can only come back from the host tier
+        scribble = W.f32_to_bf16_bits(self.rng.standard_normal((n, 2, HKV, P, D)).astype(np.float32))
+        self.mirror[ids] = scribble
+        self.pool[torch.tensor(ids, device="cuda")] = to_torch(scribble)
+        for nid in nodes:
+            self.free_gpu += self.gpu_pages.pop(nid)
+        self.rng.shuffle(self.free_gpu)
+
+    def swap_in(self, nodes):
+        """These host nodes come back (prefetch or hit): one pbkv_swap_in_pages call into free slots."""
+        src, dst = [], []
+        for nid in nodes:
+            ids = [self.free_gpu.pop() for _ in self.host_slots[nid]]
+            src += self.host_slots[nid]
+            dst += ids
+            self.gpu_pages[nid] = ids
+        staging = torch.stack([self.host[s] for s in src]).pin_memory()
+        binding.swap_in_pages(self.shape, staging, np.array(dst, np.int32), self.pool)
+        torch.cuda.synchronize()
+        self.mirror = self.oracle.swap_in(self.host_mirror[src], np.array(dst, np.int32), self.mirror)
+        for nid in nodes:
+            self.free_host += self.host_slots.pop(nid)
+        assert np.array_equal(to_numpy(self.pool), self.mirror)
+
+
+def test_policy_decisions_drive_the_page_movers_and_attention(oracle):
+    st = TwoTier(oracle, seed=77)
+    pol = PC.Policy(num_agents=3, horizon=2, gamma=0.7)
+    # radix tree: system prompt 0; agent descriptions 1, 2; private chains of three workflows
+    tree = {0: (-1, 3), 1: (0, 2), 2: (0, 2), 10: (1, 3), 11: (10, 2), 20: (2, 4), 30: (1, 3), 31: (30, 2)}
+    for nid, (parent, pages) in tree.items():
+        pol.node_add(nid, parent, pages)
+        st.create(nid, pages)
+    assert len(st.free_gpu) == NP_GPU - 21
+    pol.access(100, 0, [0, 1, 10, 11])         # workflow 100, agent 0
+    pol.access(200, 1, [0, 2, 20])             # workflow 200, agent 1
+    pol.access(300, 0, [0, 1, 30, 31])         # workflow 300, agent 0
+    never, soon = [[0.0, 0.0, 0.0, 1.0]] * 2, [[0.9, 0.0, 0.0, 0.1], [0.5, 0.0, 0.0, 0.5]]
+    pol.forecast(100, soon)                    # agent 0 of workflow 100 is about to run again
+    pol.forecast(200, [[0.0, 0.2, 0.0, 0.8], [0.0, 0.1, 0.0, 0.9]])
+    pol.forecast(300, never)
+
+    # memory pressure: 7 pages must go; the cold chain of workflow 300 and part of 200 leave
+    evicted, freed = pol.evict(7, to_host=True)
+    assert evicted == [31, 30, 20] and freed == 9
+    st.swap_out(evicted)
+
+    # workflow 300 wakes up: its forecast now points at agent 0 and a pure-decode batch prefetches
+    pol.forecast(300, soon)
+    pol.observe_transfer(50e9 * 1e-3, 1e-3)
+    pol.observe_step(0.4e-3)                   # 20 MB per step = 305 pages of 64 KiB
+    budget = pol.bandwidth_budget_pages(65536)
+    assert budget == 305
+    loads, reclaimed = pol.prefetch(len(st.free_gpu), budget, pure_decode=True)
+    assert loads == [30, 31, 20] and reclaimed == []      # Value 0.9, 0.9 (once its parent is back), 0.2
+    st.swap_in(loads)
+    assert len(st.free_gpu) == 3
+
+    # workflow 200 terminates, 100 keeps going; then agent 0 of workflow 300 runs with 40 new tokens
+    pol.terminate(200)
+    assert pol.is_retired(2) and not pol.is_retired(0)
+    path = [0, 1, 30, 31]
+    assert all(pol.node_tier(n) == PC.GPU for n in path)
+    for n in path:
+        pol.node_pin(n, 1)
+    pages = [pg for n in path for pg in st.gpu_pages[n]]
+    p_len, n_new = len(pages) * P, 40
+    q = W.f32_to_bf16_bits(st.rng.standard_normal((n_new, HQ, D)).astype(np.float32) * 0.7)
+    k_new = W.f32_to_bf16_bits(st.rng.standard_normal((n_new, HKV, D)).astype(np.float32) * 0.7)
+    v_new = W.f32_to_bf16_bits(st.rng.standard_normal((n_new, HKV, D)).astype(np.float32) * 0.7)
+    table = np.zeros((1, 16), np.int32)
+    table[0, :len(pages)] = pages
+    plens, nlens = np.array([p_len], np.int32), np.array([n_new], np.int32)
+    out = torch.zeros((n_new, HQ, D), dtype=torch.bfloat16, device="cuda")
+    binding.prefix_prefill(st.shape, to_torch(q), to_torch(k_new), to_torch(v_new), st.pool, to_torch(table),
+                           plens, nlens, out)
+    torch.cuda.synchronize()
+    got = W.to_f64(to_numpy(out))
+    want = oracle.prefill(q, k_new, v_new, st.mirror, table, plens, nlens)
+    assert_close(got, want, "bf16", "attention over the re-assembled prefix")
+    # brute force over the node contents: never sees a page id, a host slot or a swap
+    b = W.Batch(name="loop", dtype="bf16", Hq=HQ, Hkv=HKV, d=D, P=P, num_pages=NP_GPU, q=q, k_new=k_new, v_new=v_new,
+                kv_pool=st.mirror, block_table=table, prefix_lens=plens, new_lens=nlens,
+                logical_k=[np.concatenate([st.kv[n][0] for n in path] + [k_new])],
+                logical_v=[np.concatenate([st.kv[n][1] for n in path] + [v_new])])
+    ref, _ = bruteforce.attention(b)
+    np.testing.assert_allclose(want, ref, atol=1e-12)
+    for n in path:
+        pol.node_pin(n, -1)
+
+    # the retired branch of workflow 200 is what the next eviction takes, before any active node
+    evicted, freed = pol.evict(1, to_host=False)
+    assert evicted == [20] and freed == 4
