@@ -154,3 +154,30 @@ def swap_out(kv_pool, page_ids):
     if rc != 0:
         raise ValueError("oracle rejected its arguments (code %d)" % rc)
     return host
+
+
+def decode(q, kv_pool, block_table, context_lens):
+    """Paged decode attention (Sec. 4.3: the pure-decode steps behind which prefetch transfers
+    are hidden): one query row per request attends to the request's first context_lens[r]
+    cached tokens, all read through the block table.  This is the prefill definition above
+    with one new token whose own K/V are the pool's entries at position L-1; requests with
+    context_lens[r] == 0 give a zero row.  q: [B, Hq, d]; returns float64 [B, Hq, d]."""
+    pool = np.asarray(kv_pool)
+    lens = np.asarray(context_lens, np.int64)
+    B, P = lens.shape[0], pool.shape[3]
+    Hkv, d = pool.shape[2], pool.shape[4]
+    live = np.nonzero(lens > 0)[0]
+    out = np.zeros((B,) + tuple(np.asarray(q).shape[1:]), np.float64)
+    if live.size == 0:
+        return out
+    k_last = np.zeros((live.size, Hkv, d), pool.dtype)
+    v_last = np.zeros((live.size, Hkv, d), pool.dtype)
+    for i, r in enumerate(live):
+        pos = int(lens[r]) - 1
+        pg = int(np.asarray(block_table)[r, pos // P])
+        k_last[i] = pool[pg, 0, :, pos % P]
+        v_last[i] = pool[pg, 1, :, pos % P]
+    res = prefill(np.asarray(q)[live], k_last, v_last, pool, np.asarray(block_table)[live],
+                  (lens[live] - 1).astype(np.int32), np.ones(live.size, np.int32))
+    out[live] = res
+    return out

@@ -284,3 +284,23 @@ def test_swap_out_matches_fancy_index_and_round_trips(oracle):
     assert np.array_equal(back[dst], b.kv_pool[ids])
     with pytest.raises(ValueError):
         oracle.swap_out(b.kv_pool, np.array([b.num_pages], np.int32))
+
+
+def test_decode_is_a_softmax_weighted_mean_over_the_paged_context(oracle):
+    """Decode rows (one query per request over its whole paged context) against a textbook
+    softmax-weighted mean over the contiguous K/V that the generator kept before paging."""
+    from scipy.special import softmax
+    b = W.ragged_small(61, "bf16", Hq=8, Hkv=2, d=64, prefix_lens=(1, 16, 37, 130, 0), new_lens=(1, 1, 1, 1, 1))
+    lens = b.prefix_lens.copy()
+    q = b.q                                    # one row per request: [5, Hq, d]
+    out = oracle.decode(q, b.kv_pool, b.block_table, lens)
+    G = b.Hq // b.Hkv
+    for r in range(b.B):
+        L = int(lens[r])
+        if L == 0:
+            assert not out[r].any()
+            continue
+        K, V = W.to_f64(b.logical_k[r][:L]), W.to_f64(b.logical_v[r][:L])
+        for h in range(b.Hq):
+            w = softmax(W.to_f64(q[r, h]) @ K[:, h // G].T / np.sqrt(b.d))
+            np.testing.assert_allclose(out[r, h], w @ V[:, h // G], atol=1e-12)
