@@ -145,6 +145,34 @@ def swap_out_rate(db, torch, binding, reps=3):
             "pinned_d2h_memcpy_GBps": host.numel() * host.element_size() / ceil / 1e9}
 
 
+def decode_rate(torch, binding, W, DeviceBatch, reps=20):
+    """Paged decode attention on a pure-decode batch: the HBM-bound step behind which prefetch
+    transfers are hidden.  Algorithmic bytes = every K and V row of every context once
+    (+ q and out, negligible)."""
+    b = W.decode_batch()
+    db = DeviceBatch(b)
+    out = torch.zeros_like(db.q)
+    lens = np.ascontiguousarray(b.prefix_lens, np.int32)
+    kv_bytes = int(lens.sum()) * 2 * b.Hkv * b.d * b.elt
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(3):
+        binding.paged_decode(db.shape, db.q, db.kv_pool, db.block_table, lens, out)
+    torch.cuda.synchronize()
+    times = []
+    for _ in range(reps):
+        e0.record()
+        binding.paged_decode(db.shape, db.q, db.kv_pool, db.block_table, lens, out)
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1) * 1e-3)
+    t = float(np.median(times))
+    return {"workload": "decode_batch: 64 requests, contexts U{1024..16384} (%d tokens), 32/8 heads, d=128" % int(lens.sum()),
+            "step_ms": t * 1e3, "min_ms": min(times) * 1e3, "kv_bytes": kv_bytes,
+            "roofline": {"bound": "hbm", "achieved": kv_bytes / t / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": kv_bytes / t / 1e9 / PEAK_HBM_GBS},
+            "tokens_per_s": b.B / t}
+
+
 def policy_latency(steps=6000, warm=3000, concurrency=72):
     """Per-call latency of the policy core (host C++) on the synthetic workflow driver at the
     paper's operating point of 72 concurrent workflows (App. F, Table of scheduler overhead),
@@ -360,6 +388,10 @@ def main():
                 torch.cuda.empty_cache()
             except Exception as e:                      # the headline line must still print
                 extra[name] = {"error": repr(e)}
+        try:
+            extra["decode"] = decode_rate(torch, binding, W, DeviceBatch)
+        except Exception as e:
+            extra["decode"] = {"error": repr(e)}
         try:
             extra["policy"] = policy_latency()
         except Exception as e:

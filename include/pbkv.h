@@ -131,6 +131,24 @@ int pbkv_swap_in_pages(const pbkv_shape *shape, const void *host_pages,
                        void *stream);
 
 /*
+ * Paged decode attention (Sec. 4.3: prefetch transfers are hidden behind pure-decode steps, so
+ * the decode step is what the transfer budget Bandwidth * StepDuration is measured against).
+ * One query row per request: for request r and query head h,
+ *     out[r][h] = sum_t softmax_t(q[r][h] . k_t / sqrt(d)) v_t   over t in [0, context_lens[r])
+ * with k_t, v_t read from kv_pool through block_table[r] (KV head h / (H_q / H_kv)); the row's own
+ * token is expected to be in the pool already (append first).  context_lens[r] == 0 gives a zero row.
+ *   q, out      : device, [batch][H_q][d], bf16 (other dtypes: PBKV_ERR_DTYPE)
+ *   kv_pool, block_table : device, read only;   context_lens : host int32 [batch]
+ * fp32 accumulation, probabilities kept in fp32, one final rounding to bf16.  The library keeps a
+ * device scratch buffer for the partial results of context slices (allocated on first use, grown
+ * on demand); calls on different streams of one device must not overlap.
+ * Errors: NULL pointers, unsupported shape, negative lengths, ceil(len / P) > max_pages_per_req.
+ */
+int pbkv_paged_decode(const pbkv_shape *shape, const void *q, const void *kv_pool,
+                      const int32_t *block_table, const int32_t *context_lens, void *out,
+                      void *stream);
+
+/*
  * Pool -> host page swap-out (Sec. 2: with HiCache, cache evicted from the GPU is retained
  * in host memory), the mirror of pbkv_swap_in_pages: host page i := pool page
  * page_ids[i], whole pages, byte-exact; the pool is not modified.

@@ -50,6 +50,8 @@ def load():
         lib.pbkv_append_kv.argtypes = [sp, vp, vp, vp, i32p, i32p, i32p, vp]
         lib.pbkv_swap_in_pages.restype = ctypes.c_int
         lib.pbkv_swap_in_pages.argtypes = [sp, vp, i32p, ctypes.c_int32, vp, vp]
+        lib.pbkv_paged_decode.restype = ctypes.c_int
+        lib.pbkv_paged_decode.argtypes = [sp, vp, vp, i32p, i32p, vp, vp]
         lib.pbkv_swap_out_pages.restype = ctypes.c_int
         lib.pbkv_swap_out_pages.argtypes = [sp, vp, i32p, ctypes.c_int32, vp, vp]
         lib.pbkv_gather_probe.restype = ctypes.c_int
@@ -127,6 +129,12 @@ def swap_in_pages(shape, host_pages, page_ids, kv_pool, stream=None):
     ids, idp = _host_i32(page_ids)
     _check(load().pbkv_swap_in_pages(ctypes.byref(shape), _ptr(host_pages), idp,
                                      int(ids.shape[0]), _ptr(kv_pool), _stream(stream)))
+
+
+def paged_decode(shape, q, kv_pool, block_table, context_lens, out, stream=None):
+    cl, clp = _host_i32(context_lens)
+    _check(load().pbkv_paged_decode(ctypes.byref(shape), _ptr(q), _ptr(kv_pool), _ptr(block_table), clp,
+                                    _ptr(out), _stream(stream)))
 
 
 def swap_out_pages(shape, kv_pool, page_ids, host_pages, stream=None):

@@ -190,6 +190,33 @@ int ring_release(const Lease &l, hipStream_t s) {
     return PBKV_OK;
 }
 
+// Device scratch of the decode kernels (partials of the context slices): one buffer per device,
+// grown on demand and kept until the process ends.  Calls that use it must not overlap on
+// different streams of one device.
+int decode_scratch(size_t bytes, float **out) {
+    static std::mutex mu;
+    static std::vector<std::pair<void *, size_t>> per_device;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    std::lock_guard<std::mutex> lock(mu);
+    if ((int)per_device.size() <= dev) per_device.resize(dev + 1, {nullptr, 0});
+    auto &slot = per_device[dev];
+    if (slot.second < bytes) {
+        if (slot.first) {
+            if ((e = hipDeviceSynchronize()) != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
+            (void)hipFree(slot.first);
+            slot = {nullptr, 0};
+        }
+        const size_t cap = std::max(bytes + bytes / 2, (size_t)4 << 20);
+        void *ptr = nullptr;
+        if ((e = hipMalloc(&ptr, cap)) != hipSuccess) return fail_hip(e, "hipMalloc (decode scratch)");
+        slot = {ptr, cap};
+    }
+    *out = (float *)slot.first;
+    return PBKV_OK;
+}
+
 // Work list of the attention kernels: one tile per block of T suffix tokens of a request,
 // longest (most visible keys) first; `pad` keeps the tile's index in request order.
 int build_tiles(const pbkv_shape *s, const int32_t *prefix_lens, const int32_t *new_lens, int T,
@@ -400,6 +427,74 @@ int pbkv_swap_in_pages(const pbkv_shape *s, const void *host_pages, const int32_
                                         pbkv_page_bytes(s), st);
     int rel = ring_release(lease, st);
     if (e != hipSuccess) return fail_hip(e, "swap-in launch");
+    return rel;
+}
+
+int pbkv_paged_decode(const pbkv_shape *s, const void *q, const void *kv_pool, const int32_t *block_table,
+                      const int32_t *context_lens, void *out, void *stream) {
+    g_err[0] = 0;
+    int rc = check_shape(s, true);
+    if (rc) return rc;
+    if (s->dtype != PBKV_BF16) return fail(PBKV_ERR_DTYPE, "pbkv_paged_decode: bf16 only");
+    if (s->batch == 0) return PBKV_OK;
+    if (!q || !kv_pool || !block_table || !context_lens || !out)
+        return fail(PBKV_ERR_NULL, "pbkv_paged_decode: NULL argument");
+    const int B = s->batch, P = s->page_size;
+    int64_t total_pages = 0;
+    for (int r = 0; r < B; r++) {
+        const int64_t L = context_lens[r];
+        if (L < 0 || L > INT32_MAX - 4096) return fail(PBKV_ERR_RANGE, "request %d: context length %lld", r, (long long)L);
+        const int64_t pages = (L + P - 1) / P;
+        if (pages > s->max_pages_per_req)
+            return fail(PBKV_ERR_RANGE, "request %d needs %lld pages, block_table rows hold %d", r, (long long)pages,
+                        s->max_pages_per_req);
+        total_pages += pages;
+    }
+    if ((rc = check_aligned(q, "q")) || (rc = check_aligned(kv_pool, "kv_pool")) || (rc = check_aligned(out, "out"))) return rc;
+    if ((rc = check_device_ptr(q, "q")) || (rc = check_device_ptr(kv_pool, "kv_pool")) ||
+        (rc = check_device_ptr(block_table, "block_table")) || (rc = check_device_ptr(out, "out")))
+        return rc;
+
+    // slices: enough work-groups to fill the chip a few times over, at least 16 pages each
+    const int G = s->num_q_heads / s->num_kv_heads;
+    const int per_unit = s->num_kv_heads * (G / pbkv::decode_heads_per_group(G));   // work-groups per slice
+    int64_t pps = (total_pages * per_unit + 2047) / 2048;
+    pps = std::max<int64_t>(16, (pps + 3) & ~(int64_t)3);
+    std::vector<pbkv::DecodeUnit> units;
+    std::vector<pbkv::DecodeReq> reqs((size_t)B);
+    for (int r = 0; r < B; r++) {
+        const int32_t L = context_lens[r];
+        const int32_t pages = (L + P - 1) / P;
+        reqs[r] = pbkv::DecodeReq{(int32_t)units.size(), 0, {0, 0}};
+        for (int32_t p0 = 0; p0 < pages; p0 += (int32_t)pps) {
+            const int32_t p1 = (int32_t)std::min<int64_t>(pages, p0 + pps);
+            units.push_back(pbkv::DecodeUnit{r, L, p0, p1, (int32_t)units.size(), {0, 0, 0}});
+            reqs[r].n_splits++;
+        }
+    }
+    if (units.size() > (size_t)INT32_MAX / 64) return fail(PBKV_ERR_LIMIT, "too many slices");
+
+    hipStream_t st = (hipStream_t)stream;
+    float *scratch = nullptr;
+    const size_t need = std::max<size_t>(units.size(), 1) * per_unit * 4 * pbkv::decode_partial_floats(s->head_dim, G) * sizeof(float);
+    if ((rc = decode_scratch(need, &scratch))) return rc;
+
+    Lease lease;
+    const size_t ub = units.size() * sizeof(pbkv::DecodeUnit), rb = reqs.size() * sizeof(pbkv::DecodeReq);
+    if ((rc = ring_acquire(ub + rb, &lease))) return rc;
+    memcpy(lease.host, units.data(), ub);
+    memcpy((char *)lease.host + ub, reqs.data(), rb);
+    pbkv::DecodeParams p;
+    p.q = q; p.kv_pool = kv_pool; p.out = out; p.block_table = block_table;
+    p.units = (const pbkv::DecodeUnit *)lease.dev;
+    p.reqs = (const pbkv::DecodeReq *)((const char *)lease.dev + ub);
+    p.scratch = scratch;
+    p.n_units = (int32_t)units.size(); p.n_reqs = B;
+    p.Hq = s->num_q_heads; p.Hkv = s->num_kv_heads;
+    p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
+    hipError_t e = pbkv::launch_decode_bf16(p, s->head_dim, st);
+    int rel = ring_release(lease, st);
+    if (e != hipSuccess) return fail_hip(e, "decode launch");
     return rel;
 }
 

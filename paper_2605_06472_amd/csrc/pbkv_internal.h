@@ -42,6 +42,32 @@ struct AttnParams {
     void *trace;   // development instrumentation; unused unless built with it
 };
 
+// Decode: one slice of a request's context pages, shared by its KV heads and head groups.
+struct DecodeUnit {
+    int32_t req;         // request index (row of q / out / block_table)
+    int32_t ctx_len;     // tokens the request's row attends to
+    int32_t page0, page1;  // logical pages [page0, page1) of this slice
+    int32_t split;       // running index of the slice over the whole call (addresses the scratch)
+    int32_t pad[3];
+};
+static_assert(sizeof(DecodeUnit) == 32, "DecodeUnit is read as two 16-byte words");
+
+struct DecodeReq {
+    int32_t split0, n_splits;   // the request's slices are split0 .. split0 + n_splits - 1
+    int32_t pad[2];
+};
+static_assert(sizeof(DecodeReq) == 16, "DecodeReq is read as one 16-byte word");
+
+struct DecodeParams {
+    const void *q, *kv_pool;
+    void *out;
+    const int32_t *block_table;
+    const DecodeUnit *units;
+    const DecodeReq *reqs;
+    float *scratch;
+    int32_t n_units, n_reqs, Hq, Hkv, max_pages, num_pages;
+};
+
 struct AppendParams {
     const void *k_new, *v_new;
     void *kv_pool;
@@ -65,6 +91,11 @@ int attn_bf16_units_per_tile(int num_kv_heads, int group);
 hipError_t launch_append(const AppendParams &p, int head_dim, int elt_bytes, hipStream_t s);
 hipError_t launch_swap_in(const void *host_pages, const int32_t *page_ids_dev, int32_t n_pages,
                           void *kv_pool, int64_t page_bytes, hipStream_t s);
+
+// Paged decode attention (bf16): main kernel + merge of the partials in p.scratch.
+hipError_t launch_decode_bf16(const DecodeParams &p, int head_dim, hipStream_t s);
+int decode_heads_per_group(int group);
+int64_t decode_partial_floats(int head_dim, int group);   // floats one wave's partial occupies
 
 hipError_t launch_swap_out(const void *kv_pool, const int32_t *page_ids_dev, int32_t n_pages,
                            void *host_pages, int64_t page_bytes, hipStream_t s);

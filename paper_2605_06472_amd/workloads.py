@@ -356,6 +356,17 @@ def ragged_small(seed: int, dtype: str = "bf16", Hq: int = 8, Hkv: int = 2, d: i
                      nonresident=nonresident, page_perm=page_perm)
 
 
+def decode_batch(seed: int = 1005, batch: int = 64, min_ctx: int = 1024, max_ctx: int = 16384,
+                 num_pages: int = 40960, q_scale: float = 1.0) -> Batch:
+    """A pure-decode batch (the steps behind which prefetch transfers are hidden): every request
+    contributes one query row over a private, fully scattered context of U{min_ctx..max_ctx}
+    tokens (prefix_lens holds the context lengths; new_lens is all ones and only sizes q)."""
+    rng = np.random.Generator(np.random.Philox(np.random.SeedSequence([seed, 17])))
+    ctx = [int(rng.integers(min_ctx, max_ctx + 1)) for _ in range(batch)]
+    return _assemble("decode_batch", "bf16", 32, 8, 128, num_pages, seed, 2 ** -0.5,
+                     [[_seg(c)] for c in ctx], [1] * batch, q_scale=q_scale)
+
+
 CONFIGS = {
     "cfg0": tiny_fp32,
     "cfg1": shared_system_prompt,
