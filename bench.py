@@ -281,6 +281,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", default="cfg1", choices=["cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads and the CPU baseline")
+    ap.add_argument("--part", default=None, choices=["decode", "policy"],
+                    help="run only this secondary measurement and print its JSON object (for profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 256 MiB device-to-device copies (known HBM traffic) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command can be scaled")
@@ -308,6 +310,13 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.part == "decode":
+        print(json.dumps(decode_rate(torch, binding, W, DeviceBatch)))
+        return
+    if args.part == "policy":
+        print(json.dumps(policy_latency()))
+        return
 
     b, db, wall, kern_ms = time_config(args.config, args.steps, args.warmup, torch, binding, W, DeviceBatch)
     ms_per_step = wall / args.steps * 1e3

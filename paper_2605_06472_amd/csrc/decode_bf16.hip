@@ -5,8 +5,8 @@
 // Work decomposition
 //   work-group = 4 waves = (request, slice of its pages, KV head, group of <= 8 query heads).
 //   A wave takes every fourth page of the slice and keeps the K and V rows of the NEXT page in
-//   flight (in registers) while it works on the current one: 8 KiB per wave, 16 per CU, enough
-//   outstanding bytes to cover the HBM latency.  No LDS, no barrier.
+//   flight (in registers) while it works on the current one: 8 KiB per wave, 64 per CU, enough
+//   outstanding bytes to cover the HBM latency.  No LDS traffic and no barrier inside the loop.
 //
 //   scores     S[token][head] = K Q^T on the 16x16x32 bf16 MFMA: the A operand (16 tokens x 32 d)
 //              is exactly 16 bytes per lane of a row-major K page, so K goes from global memory
@@ -17,8 +17,9 @@
 //   P V        on the vector ALU: V has d contiguous and the MFMA wants tokens contiguous, and an
 //              HBM-bound kernel has the ALU time: lane (g, x) holds 8 d-values of its group's
 //              tokens and gets their probabilities by ds_bpermute from the lanes that own them.
-//   Each wave writes its partial (reference, row sum, unnormalised output) to a scratch buffer;
-//   a small second kernel merges the partials of a request.
+//   The four waves merge their partials (reference, row sum, unnormalised output) in LDS at the
+//   very end and the work-group writes one partial to a scratch buffer; a small second kernel
+//   merges the slices of a request.
 #include "pbkv_internal.h"
 
 namespace pbkv {
@@ -97,9 +98,15 @@ void decode_bf16_kernel(DecodeParams p, int G) {
         const int pg = __builtin_amdgcn_readlane(ids, k & 63);
         const char *kb = pool_k + pg * page_bytes;
 #pragma unroll
-        for (int j = 0; j < NJ; j++) r.k[j] = *(const bf16x8 *)(kb + koff + 64 * j);
+        for (int j = 0; j < NJ; j++) {
+            // K and V are read exactly once: streaming loads
+            const u32x4 raw = __builtin_nontemporal_load((const u32x4 *)(kb + koff + 64 * j));
+            __builtin_memcpy(&r.k[j], &raw, 16);
+        }
 #pragma unroll
-        for (int i = 0; i < NLV; i++) r.v[i] = *(const u32x4 *)(kb + v_in_page + voff + i * RPL * ROWB);
+        for (int i = 0; i < NLV; i++) {
+            r.v[i] = __builtin_nontemporal_load((const u32x4 *)(kb + v_in_page + voff + i * RPL * ROWB));
+        }
     };
 
     float acc[GW][8];
@@ -173,15 +180,26 @@ void decode_bf16_kernel(DecodeParams p, int G) {
         }
     };
 
-    PageRegs ra, rb;
-    if (n_mine > 0) load_page(0, ra);
-    for (int k = 0; k < n_mine; k += 2) {
-        if (k + 1 < n_mine) load_page(k + 1, rb);
-        compute_page(k, ra);
-        if (k + 1 < n_mine) {
-            if (((k + 2) & 63) == 0) ids = load_ids((k + 2) >> 6);
-            if (k + 2 < n_mine) load_page(k + 2, ra);
-            compute_page(k + 1, rb);
+#ifndef DEC_NBUF
+#define DEC_NBUF 2
+#endif
+    // the pages NBUF-1 ahead are in flight while one is being worked on
+    PageRegs rg[DEC_NBUF];
+#pragma unroll
+    for (int b = 0; b < DEC_NBUF - 1; b++)
+        if (b < n_mine) load_page(b, rg[b]);
+    for (int k0 = 0; k0 < n_mine; k0 += DEC_NBUF) {
+#pragma unroll
+        for (int b = 0; b < DEC_NBUF; b++) {
+            const int k = k0 + b;
+            if (k < n_mine) {
+                const int kn = k + DEC_NBUF - 1;
+                if (kn < n_mine) {
+                    if ((kn & 63) == 0) ids = load_ids(kn >> 6);
+                    load_page(kn, rg[(b + DEC_NBUF - 1) % DEC_NBUF]);
+                }
+                compute_page(k, rg[b]);
+            }
         }
     }
 
@@ -199,29 +217,55 @@ void decode_bf16_kernel(DecodeParams p, int G) {
     lsum += __shfl_xor(lsum, 16, 64);
     lsum += __shfl_xor(lsum, 32, 64);
 
-    // partial of this wave: [GW][D] output, [GW] reference, [GW] row sum
-    const int64_t slot = ((((int64_t)un.split * p.Hkv + kvh) * nsplit_g + hs) * DEC_WAVES + w);
+    // the four waves of the work-group meet in LDS; the work-group stores ONE partial:
+    // [GW][D] unnormalised output, [GW] reference, [GW] row sum
     constexpr int PS = (GW * (D + 2) + 3) & ~3;
-    float *ps = p.scratch + slot * PS;
-    if (g == 0 && sub == 0) {
+    __shared__ __attribute__((aligned(16))) float part[DEC_WAVES][PS];
+    {
+        float *ps = part[w];
+        if (g == 0 && sub == 0) {
 #pragma unroll
-        for (int h = 0; h < GW; h++) {
-            float *o = ps + h * D + 8 * (l % CPR);
-            *(f32x4 *)o = f32x4{acc[h][0], acc[h][1], acc[h][2], acc[h][3]};
-            *(f32x4 *)(o + 4) = f32x4{acc[h][4], acc[h][5], acc[h][6], acc[h][7]};
+            for (int h = 0; h < GW; h++) {
+                float *o = ps + h * D + 8 * (l % CPR);
+                *(f32x4 *)o = f32x4{acc[h][0], acc[h][1], acc[h][2], acc[h][3]};
+                *(f32x4 *)(o + 4) = f32x4{acc[h][4], acc[h][5], acc[h][6], acc[h][7]};
+            }
+        }
+        if (g == 0 && c < GW) {
+            ps[GW * D + c] = M;
+            ps[GW * D + GW + c] = lsum;
         }
     }
-    if (g == 0 && c < GW) {
-        ps[GW * D + c] = M;
-        ps[GW * D + GW + c] = lsum;
+    __syncthreads();
+    const int64_t slot = (((int64_t)un.split * p.Hkv + kvh) * nsplit_g + hs);
+    float *dst = p.scratch + slot * PS;
+    for (int idx = threadIdx.x; idx < GW * D + GW; idx += 64 * DEC_WAVES) {
+        const int h = idx < GW * D ? idx / D : idx - GW * D;
+        float Mx = -INFINITY;
+#pragma unroll
+        for (int ww = 0; ww < DEC_WAVES; ww++) Mx = fmaxf(Mx, part[ww][GW * D + h]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < DEC_WAVES; ww++) {
+            const float m = part[ww][GW * D + h];
+            const float f = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - Mx);   // a wave without pages
+            num += f * (idx < GW * D ? part[ww][idx] : 0.f);
+            den += f * part[ww][GW * D + GW + h];
+        }
+        if (idx < GW * D) {
+            dst[idx] = num;
+        } else {
+            dst[GW * D + h] = Mx;
+            dst[GW * D + GW + h] = den;
+        }
     }
 #endif
 }
 
-// One work-group per (request, KV head, head group): merges the partials of the request's
-// slices and waves, normalises and rounds once to bf16.
+// One work-group per (request, KV head, head group), one thread per (head, d): merges the
+// partials of the request's slices, normalises and rounds once to bf16.
 template <int D, int GW>
-__global__ __launch_bounds__(D) void decode_merge_kernel(DecodeParams p, int G) {
+__global__ __launch_bounds__(D * GW) void decode_merge_kernel(DecodeParams p, int G) {
     const int nsplit_g = G / GW;
     int bid = blockIdx.x;
     const int hs = bid % nsplit_g;
@@ -229,29 +273,22 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeParams p, int G) 
     const int kvh = bid % p.Hkv;
     const int req = bid / p.Hkv;
     const DecodeReq rq = p.reqs[req];
-    const int d = threadIdx.x;
+    const int d = threadIdx.x % D, h = threadIdx.x / D;
     constexpr int PS = (GW * (D + 2) + 3) & ~3;
-    for (int h = 0; h < GW; h++) {
-        float Mx = -INFINITY;
-        for (int s = 0; s < rq.n_splits; s++)
-            for (int w = 0; w < DEC_WAVES; w++) {
-                const int64_t slot = ((((int64_t)(rq.split0 + s) * p.Hkv + kvh) * nsplit_g + hs) * DEC_WAVES + w);
-                Mx = fmaxf(Mx, p.scratch[slot * PS + GW * D + h]);
-            }
-        float num = 0.f, den = 0.f;
-        for (int s = 0; s < rq.n_splits; s++)
-            for (int w = 0; w < DEC_WAVES; w++) {
-                const int64_t slot = ((((int64_t)(rq.split0 + s) * p.Hkv + kvh) * nsplit_g + hs) * DEC_WAVES + w);
-                const float *ps = p.scratch + slot * PS;
-                const float m = ps[GW * D + h];
-                if (m == -INFINITY) continue;                    // a wave without pages
-                const float f = exp2f(m - Mx);
-                num += f * ps[h * D + d];
-                den += f * ps[GW * D + GW + h];
-            }
-        __bf16 *o = (__bf16 *)p.out + ((int64_t)req * p.Hq + kvh * G + hs * GW + h) * D + d;
-        *o = (__bf16)(den > 0.f ? num / den : 0.f);
+    const int64_t stride = (int64_t)p.Hkv * nsplit_g * PS;             // between consecutive slices
+    const float *base = p.scratch + (((int64_t)rq.split0 * p.Hkv + kvh) * nsplit_g + hs) * PS;
+    float Mx = -INFINITY;
+    for (int s = 0; s < rq.n_splits; s++) Mx = fmaxf(Mx, base[s * stride + GW * D + h]);
+    float num = 0.f, den = 0.f;
+    for (int s = 0; s < rq.n_splits; s++) {
+        const float *ps = base + s * stride;
+        const float m = ps[GW * D + h];
+        const float f = m == -INFINITY ? 0.f : exp2f(m - Mx);
+        num += f * ps[h * D + d];
+        den += f * ps[GW * D + GW + h];
     }
+    __bf16 *o = (__bf16 *)p.out + ((int64_t)req * p.Hq + kvh * G + hs * GW + h) * D + d;
+    *o = (__bf16)(den > 0.f ? num / den : 0.f);
 }
 
 template <int D, int GW>
@@ -263,7 +300,7 @@ static hipError_t launch_decode_one(const DecodeParams &p, int G, hipStream_t s)
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((decode_merge_kernel<D, GW>), dim3((unsigned)p.n_reqs * p.Hkv * nsplit_g), dim3(D), 0, s, p, G);
+    hipLaunchKernelGGL((decode_merge_kernel<D, GW>), dim3((unsigned)p.n_reqs * p.Hkv * nsplit_g), dim3(D * GW), 0, s, p, G);
     return hipGetLastError();
 }
 

@@ -458,7 +458,8 @@ int pbkv_paged_decode(const pbkv_shape *s, const void *q, const void *kv_pool, c
     // slices: enough work-groups to fill the chip a few times over, at least 16 pages each
     const int G = s->num_q_heads / s->num_kv_heads;
     const int per_unit = s->num_kv_heads * (G / pbkv::decode_heads_per_group(G));   // work-groups per slice
-    int64_t pps = (total_pages * per_unit + 2047) / 2048;
+    static const int64_t target_wgs = [] { const char *e = getenv("PBKV_DECODE_WGS"); return e && atoi(e) > 0 ? (int64_t)atoi(e) : (int64_t)2048; }();
+    int64_t pps = (total_pages * per_unit + target_wgs - 1) / target_wgs;
     pps = std::max<int64_t>(16, (pps + 3) & ~(int64_t)3);
     std::vector<pbkv::DecodeUnit> units;
     std::vector<pbkv::DecodeReq> reqs((size_t)B);
@@ -476,7 +477,7 @@ int pbkv_paged_decode(const pbkv_shape *s, const void *q, const void *kv_pool, c
 
     hipStream_t st = (hipStream_t)stream;
     float *scratch = nullptr;
-    const size_t need = std::max<size_t>(units.size(), 1) * per_unit * 4 * pbkv::decode_partial_floats(s->head_dim, G) * sizeof(float);
+    const size_t need = std::max<size_t>(units.size(), 1) * per_unit * pbkv::decode_partial_floats(s->head_dim, G) * sizeof(float);
     if ((rc = decode_scratch(need, &scratch))) return rc;
 
     Lease lease;

@@ -95,7 +95,7 @@ hipError_t launch_swap_in(const void *host_pages, const int32_t *page_ids_dev, i
 // Paged decode attention (bf16): main kernel + merge of the partials in p.scratch.
 hipError_t launch_decode_bf16(const DecodeParams &p, int head_dim, hipStream_t s);
 int decode_heads_per_group(int group);
-int64_t decode_partial_floats(int head_dim, int group);   // floats one wave's partial occupies
+int64_t decode_partial_floats(int head_dim, int group);   // floats one work-group's partial occupies
 
 hipError_t launch_swap_out(const void *kv_pool, const int32_t *page_ids_dev, int32_t n_pages,
                            void *host_pages, int64_t page_bytes, hipStream_t s);
