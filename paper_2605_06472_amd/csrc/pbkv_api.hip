@@ -12,6 +12,7 @@
 #include <cstring>
 #include <deque>
 #include <mutex>
+#include <string>
 #include <vector>
 
 namespace {
@@ -121,6 +122,7 @@ int check_pinned_ptr(const void *p, const char *name, const void **dev_view) {
 struct Ring {
     char *host = nullptr;
     char *dev = nullptr;
+    char *mirror = nullptr;          // device-memory copy of the ring (descriptor placement "device")
     size_t cap = 0, head = 0;
     struct Pending { hipEvent_t ev; size_t begin, end; };
     std::deque<Pending> pending;
@@ -132,6 +134,16 @@ constexpr int MAX_DEVICES = 16;
 Ring g_rings[MAX_DEVICES];
 
 struct Lease { Ring *ring; size_t begin, end; char *host; char *dev; };
+
+// Where kernels read their work lists from.  Default: the pinned ring itself, through its
+// device-mapped address (no copy in front of a kernel).  PBKV_DESCRIPTORS=device: a
+// device-memory mirror, filled by a small stream-ordered copy per call -- for callers that run
+// kernels beside bulk host-link traffic, where a work-group's descriptor read over the link
+// would queue behind that traffic.
+bool descriptors_in_device_memory() {
+    static const bool v = [] { const char *e = getenv("PBKV_DESCRIPTORS"); return e && std::string(e) == "device"; }();
+    return v;
+}
 
 int ring_acquire(size_t bytes, Lease *out) {
     int dev = 0;
@@ -149,6 +161,12 @@ int ring_acquire(size_t bytes, Lease *out) {
         r.host = (char *)h;
         r.dev = (char *)d;
         r.cap = RING_BYTES;
+        if (descriptors_in_device_memory()) {
+            void *m = nullptr;
+            e = hipMalloc(&m, RING_BYTES);
+            if (e != hipSuccess) return fail_hip(e, "hipMalloc(descriptor ring mirror)");
+            r.mirror = (char *)m;
+        }
     }
     bytes = (bytes + 255) & ~(size_t)255;
     if (bytes > r.cap / 2) return fail(PBKV_ERR_LIMIT, "work list of %zu bytes exceeds the descriptor ring", bytes);
@@ -168,8 +186,17 @@ int ring_acquire(size_t bytes, Lease *out) {
         }
     }
     r.head = en;
-    *out = Lease{&r, b, en, r.host + b, r.dev + b};
+    *out = Lease{&r, b, en, r.host + b, (r.mirror ? r.mirror : r.dev) + b};
     return PBKV_OK;
+}
+
+// Make what the host wrote into the lease visible at lease.dev: nothing to do when the kernels
+// read the pinned ring through its mapped address, one small copy on the stream when they read
+// the device-memory mirror.
+int ring_commit(const Lease &l, size_t bytes, hipStream_t s) {
+    if (!l.ring->mirror || bytes == 0) return PBKV_OK;
+    hipError_t e = hipMemcpyAsync(l.dev, l.host, bytes, hipMemcpyHostToDevice, s);
+    return e == hipSuccess ? PBKV_OK : fail_hip(e, "hipMemcpyAsync(descriptors)");
 }
 
 // Record "the kernels reading this lease are enqueued" on the stream.
@@ -290,6 +317,7 @@ int pbkv_prefix_prefill(const pbkv_shape *s, const void *q, const void *k_new, c
     p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
     p.trace = nullptr;
     hipStream_t st = (hipStream_t)stream;
+    if ((rc = ring_commit(lease, tiles.size() * sizeof(pbkv::TileDesc), st))) return rc;
     hipError_t e = s->dtype == PBKV_BF16 ? pbkv::launch_attn_bf16(p, s->head_dim, st)
                                          : pbkv::launch_attn_f32(p, s->head_dim, st);
     int rel = ring_release(lease, st);
@@ -344,6 +372,7 @@ int pbkv_gather_probe(const pbkv_shape *s, const void *k_new, const void *v_new,
     p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
     p.trace = nullptr;
     hipStream_t st = (hipStream_t)stream;
+    if ((rc = ring_commit(lease, tiles.size() * sizeof(pbkv::TileDesc), st))) return rc;
     hipError_t e = pbkv::launch_gather_probe(p, s->head_dim, st);
     int rel = ring_release(lease, st);
     if (e != hipSuccess) return fail_hip(e, "gather probe launch");
@@ -392,6 +421,7 @@ int pbkv_append_kv(const pbkv_shape *s, const void *k_new, const void *v_new, vo
     p.n_descs = (int32_t)descs.size();
     p.Hkv = s->num_kv_heads; p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
     hipStream_t st = (hipStream_t)stream;
+    if ((rc = ring_commit(lease, descs.size() * sizeof(pbkv::AppendDesc), st))) return rc;
     hipError_t e = pbkv::launch_append(p, s->head_dim, elt_bytes(s->dtype), st);
     int rel = ring_release(lease, st);
     if (e != hipSuccess) return fail_hip(e, "append launch");
@@ -423,6 +453,7 @@ int pbkv_swap_in_pages(const pbkv_shape *s, const void *host_pages, const int32_
     if ((rc = ring_acquire((size_t)n_pages * sizeof(int32_t), &lease))) return rc;
     memcpy(lease.host, page_ids, (size_t)n_pages * sizeof(int32_t));
     hipStream_t st = (hipStream_t)stream;
+    if ((rc = ring_commit(lease, (size_t)n_pages * sizeof(int32_t), st))) return rc;
     hipError_t e = pbkv::launch_swap_in(host_dev, (const int32_t *)lease.dev, n_pages, kv_pool,
                                         pbkv_page_bytes(s), st);
     int rel = ring_release(lease, st);
@@ -485,6 +516,7 @@ int pbkv_paged_decode(const pbkv_shape *s, const void *q, const void *kv_pool, c
     if ((rc = ring_acquire(ub + rb, &lease))) return rc;
     memcpy(lease.host, units.data(), ub);
     memcpy((char *)lease.host + ub, reqs.data(), rb);
+    if ((rc = ring_commit(lease, ub + rb, st))) return rc;
     pbkv::DecodeParams p;
     p.q = q; p.kv_pool = kv_pool; p.out = out; p.block_table = block_table;
     p.units = (const pbkv::DecodeUnit *)lease.dev;
@@ -521,6 +553,7 @@ int pbkv_swap_out_pages(const pbkv_shape *s, const void *kv_pool, const int32_t 
     if ((rc = ring_acquire((size_t)n_pages * sizeof(int32_t), &lease))) return rc;
     memcpy(lease.host, page_ids, (size_t)n_pages * sizeof(int32_t));
     hipStream_t st = (hipStream_t)stream;
+    if ((rc = ring_commit(lease, (size_t)n_pages * sizeof(int32_t), st))) return rc;
     hipError_t e = pbkv::launch_swap_out(kv_pool, (const int32_t *)lease.dev, n_pages, (void *)host_dev,
                                          pbkv_page_bytes(s), st);
     int rel = ring_release(lease, st);

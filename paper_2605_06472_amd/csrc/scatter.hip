@@ -40,32 +40,41 @@ hipError_t launch_append(const AppendParams &p, int head_dim, int elt_bytes, hip
     return hipGetLastError();
 }
 
-// Swap-in: each work-group moves SWAP_CHUNKS 16-byte chunks of one page from pinned host
+// Swap-in: a work-group moves SWAP_CHUNKS 16-byte chunks of one page at a time from pinned host
 // memory (read over the host link through the mapped pointer) into the page's pool slot.
-// Four independent loads per thread are in flight before the first store.
-constexpr int SWAP_CHUNKS = 1024;   // 16 KiB per work-group
+// Four independent loads per thread are in flight before the first store.  The grid is small
+// and persistent (SWAP_MAX_WGS work-groups stride over the page parts): 512 KiB in flight
+// saturates the link, and a transfer that runs beside attention or decode (Sec. 4.3: prefetch
+// hidden behind compute) must not park thousands of waves, each waiting microseconds on the
+// link, on the CUs and memory queues the compute kernel needs.
+constexpr int SWAP_CHUNKS = 1024;   // 16 KiB per work-group and pass
+#ifndef SWAP_MAX_WGS
+#define SWAP_MAX_WGS 32
+#endif
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 __global__ __launch_bounds__(256) void swap_in_kernel(const u32x4 *__restrict__ host_pages,
                                                       const int32_t *__restrict__ page_ids,
                                                       u32x4 *__restrict__ pool, int page_chunks,
-                                                      int wgs_per_page) {
-    const int page = blockIdx.x / wgs_per_page;
-    const int part = blockIdx.x % wgs_per_page;
-    const int64_t dst_page = page_ids[page];
-    const u32x4 *src = host_pages + (int64_t)page * page_chunks;
-    u32x4 *dst = pool + dst_page * page_chunks;
-    const int base = part * SWAP_CHUNKS + threadIdx.x;
-    u32x4 v[4];
+                                                      int wgs_per_page, int n_pages) {
+    for (int64_t item = blockIdx.x; item < (int64_t)n_pages * wgs_per_page; item += gridDim.x) {
+        const int page = (int)(item / wgs_per_page);
+        const int part = (int)(item % wgs_per_page);
+        const int64_t dst_page = page_ids[page];
+        const u32x4 *src = host_pages + (int64_t)page * page_chunks;
+        u32x4 *dst = pool + dst_page * page_chunks;
+        const int base = part * SWAP_CHUNKS + threadIdx.x;
+        u32x4 v[4];
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int c = base + i * 256;
-        if (c < page_chunks) v[i] = __builtin_nontemporal_load(src + c);
-    }
+        for (int i = 0; i < 4; i++) {
+            const int c = base + i * 256;
+            if (c < page_chunks) v[i] = __builtin_nontemporal_load(src + c);
+        }
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int c = base + i * 256;
-        if (c < page_chunks) dst[c] = v[i];
+        for (int i = 0; i < 4; i++) {
+            const int c = base + i * 256;
+            if (c < page_chunks) dst[c] = v[i];
+        }
     }
 }
 
@@ -74,9 +83,10 @@ hipError_t launch_swap_in(const void *host_pages, const int32_t *page_ids_dev, i
     if (n_pages == 0) return hipSuccess;
     const int page_chunks = (int)(page_bytes / 16);
     const int wgs_per_page = (page_chunks + SWAP_CHUNKS - 1) / SWAP_CHUNKS;
-    hipLaunchKernelGGL(swap_in_kernel, dim3((unsigned)n_pages * wgs_per_page), dim3(256), 0, s,
+    const int64_t items = (int64_t)n_pages * wgs_per_page;
+    hipLaunchKernelGGL(swap_in_kernel, dim3((unsigned)(items < SWAP_MAX_WGS ? items : SWAP_MAX_WGS)), dim3(256), 0, s,
                        (const u32x4 *)host_pages, page_ids_dev, (u32x4 *)kv_pool, page_chunks,
-                       wgs_per_page);
+                       wgs_per_page, n_pages);
     return hipGetLastError();
 }
 
@@ -86,23 +96,25 @@ hipError_t launch_swap_in(const void *host_pages, const int32_t *page_ids_dev, i
 __global__ __launch_bounds__(256) void swap_out_kernel(const u32x4 *__restrict__ pool,
                                                        const int32_t *__restrict__ page_ids,
                                                        u32x4 *__restrict__ host_pages, int page_chunks,
-                                                       int wgs_per_page) {
-    const int page = blockIdx.x / wgs_per_page;
-    const int part = blockIdx.x % wgs_per_page;
-    const int64_t src_page = page_ids[page];
-    const u32x4 *src = pool + src_page * page_chunks;
-    u32x4 *dst = host_pages + (int64_t)page * page_chunks;
-    const int base = part * SWAP_CHUNKS + threadIdx.x;
-    u32x4 v[4];
+                                                       int wgs_per_page, int n_pages) {
+    for (int64_t item = blockIdx.x; item < (int64_t)n_pages * wgs_per_page; item += gridDim.x) {
+        const int page = (int)(item / wgs_per_page);
+        const int part = (int)(item % wgs_per_page);
+        const int64_t src_page = page_ids[page];
+        const u32x4 *src = pool + src_page * page_chunks;
+        u32x4 *dst = host_pages + (int64_t)page * page_chunks;
+        const int base = part * SWAP_CHUNKS + threadIdx.x;
+        u32x4 v[4];
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int c = base + i * 256;
-        if (c < page_chunks) v[i] = src[c];
-    }
+        for (int i = 0; i < 4; i++) {
+            const int c = base + i * 256;
+            if (c < page_chunks) v[i] = src[c];
+        }
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int c = base + i * 256;
-        if (c < page_chunks) __builtin_nontemporal_store(v[i], dst + c);
+        for (int i = 0; i < 4; i++) {
+            const int c = base + i * 256;
+            if (c < page_chunks) __builtin_nontemporal_store(v[i], dst + c);
+        }
     }
 }
 
@@ -111,9 +123,10 @@ hipError_t launch_swap_out(const void *kv_pool, const int32_t *page_ids_dev, int
     if (n_pages == 0) return hipSuccess;
     const int page_chunks = (int)(page_bytes / 16);
     const int wgs_per_page = (page_chunks + SWAP_CHUNKS - 1) / SWAP_CHUNKS;
-    hipLaunchKernelGGL(swap_out_kernel, dim3((unsigned)n_pages * wgs_per_page), dim3(256), 0, s,
+    const int64_t items = (int64_t)n_pages * wgs_per_page;
+    hipLaunchKernelGGL(swap_out_kernel, dim3((unsigned)(items < SWAP_MAX_WGS ? items : SWAP_MAX_WGS)), dim3(256), 0, s,
                        (const u32x4 *)kv_pool, page_ids_dev, (u32x4 *)host_pages, page_chunks,
-                       wgs_per_page);
+                       wgs_per_page, n_pages);
     return hipGetLastError();
 }
 
