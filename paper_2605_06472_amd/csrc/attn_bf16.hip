@@ -68,7 +68,7 @@ constexpr int BN = 64;   // keys per LDS tile (two 32-key blocks)
 #define PBKV_PF 3
 #endif
 constexpr int PF = PBKV_PF;    // LDS operand prefetch distance, in MFMA steps
-[[maybe_unused]] constexpr float RESCALE_LOG2 = 8.0f;   // the reference maximum may lag by this much (log2)
+[[maybe_unused]] constexpr float RESCALE_SUM = 4096.0f;  // a lane's probability sum over one block above this moves the reference
 
 template <int D, int NW>
 struct Geom {
@@ -238,7 +238,7 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
     auto tile_src = [&](int t) {
         Src s;
         if (t < TP) {
-            if ((t & 15) == 0 && t > 0) {
+            if (__builtin_expect((t & 15) == 0 && t > 0, 0)) {
                 ids_cur = ids_next;
                 ids_next = load_id_block((t >> 4) + 1);
             }
@@ -300,12 +300,11 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
     for (int db = 0; db < Gm::DB; db++)
 #pragma unroll
         for (int r = 0; r < 16; r++) O[db][r] = 0.f;
-    // M: reference maximum (log2 units); negM: -M in every register of an MFMA accumulator;
-    // tmax: row max of the pending block's t; l_part: this lane's share of the row sum;
-    // alpha_pend: factor O still has to be multiplied by once the product formed under the
-    // previous reference has been added
-    float M = 0.f, tmax = 0.f, l_part = 0.f, alpha_pend = 1.f;
-    bool pend = false;
+    // negM: -M in every register of an MFMA accumulator, M being the reference (log2 units) the
+    // scores are taken relative to; l_part: this lane's share of the row sum; lb: the same for the
+    // block whose probabilities were formed last (not yet added to l_part: it is the overflow probe)
+    float l_part = 0.f, lb = 0.f;
+    bool redo = false;                                     // wave-uniform: some lane's lb is out of range
     f32x16 negM;
 #pragma unroll
     for (int r = 0; r < 16; r++) negM[r] = 0.f;
@@ -426,9 +425,10 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
     // for the product halves) from ONE stream that runs PF MFMAs ahead, across the half and
     // iteration boundaries, so only the start of a step exposes LDS latency.
     //
-    bool mv_any = false;                                   // some row maximum ran ahead of the reference
     auto step = [&](int j, char *kcur, char *knext, char *vprev, char *vcur) __attribute__((always_inline)) {
         constexpr int NM = 4 * H;                          // MFMAs per step
+        constexpr int LD_SP = H / (2 * Gm::NI);            // MFMAs between two tile loads
+        static_assert(LD_SP >= 1, "the tile loads of a step fit its first half iteration");
         TRACE_MARK(5);
         // sources: K(j+1) now, V(j) from what the previous step found for tile j
         const Src next = tile_src(j + 1);
@@ -454,33 +454,48 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
         };
         static_for([&](auto mc) { op[mc.value % (PF + 1)] = operand(mc); }, std::make_integer_sequence<int, PF>{});
 
-        auto iteration = [&](auto ic, f32x16 &Tc, f32x16 &Tn, bf16x8 (&Pc)[2], const bf16x8 (&Pp)[2], bool first) __attribute__((always_inline)) {
+        auto iteration = [&](auto ic, f32x16 &Tc, f32x16 &Tn, bf16x8 (&Pc)[2], bf16x8 (&Pp)[2], bool first_check) __attribute__((always_inline)) {
             constexpr int i = decltype(ic)::value;
             constexpr int m0 = i * 2 * H;
-            // the reference moves only when a row maximum ran ahead of it by more than 2^8 -- and at
-            // the first block, where it is set to the row maximum itself (key 0 is visible to every
-            // row, so that maximum is finite)
-            const bool mv = first || mv_any;
-            if (mv || pend) {
-                if (pend) {
+            // The common path never computes a row maximum.  The probabilities of the previous block
+            // were formed under the current reference M; their lane sum lb tells whether that was
+            // safe: a sum above 2^12 (or inf) means some score ran far ahead of M.  Then -- rarely --
+            // the block is redone: its scores are still in Tn (the score product of this iteration
+            // has not overwritten them yet), M moves up to their row maximum, O and the row sum
+            // (which hold exactly the blocks before it) are rescaled, and its probabilities are formed
+            // again.  The first block is always redone, which sets M to its row maximum whatever the
+            // magnitude of the scores (key 0 is visible to every row, so that maximum is finite).
+#if !defined(ABL_NOBRANCH) && !defined(ABL_NORESCALE)
+            if (__builtin_expect(first_check || redo, 0)) {
+                float mxp = Tn[0];
 #pragma unroll
-                    for (int db = 0; db < Gm::DB; db++)
+                for (int r = 1; r < 16; r++) mxp = fmaxf(mxp, Tn[r]);
+                mxp = xmax32(mxp);
+                const float d = first_check ? mxp : fmaxf(mxp, 0.f);      // later moves never lower the reference
+                const float alpha = first_check ? 1.f : __builtin_amdgcn_exp2f(-d);
+                l_part *= alpha;
+                // whole-vector updates: the 16-register accumulator tuples stay where they are
 #pragma unroll
-                        for (int r = 0; r < 16; r++) O[db][r] *= alpha_pend;
+                for (int db = 0; db < Gm::DB; db++) O[db] *= alpha;
+                Tn -= d;
+                Tc -= d;
+                negM -= d;
+                lb = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; r += 2) {
+                    f32x2 pv;
+                    pv[0] = __builtin_amdgcn_exp2f(Tn[r]);
+                    pv[1] = __builtin_amdgcn_exp2f(Tn[r + 1]);
+                    const bf16x2 pk = __builtin_convertvector(pv, bf16x2);
+                    Pp[r / 8][r % 8] = pk[0];
+                    Pp[r / 8][r % 8 + 1] = pk[1];
+                    lb = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lb, false);
                 }
-                pend = false;
-                if (mv) {
-                    const float d = first ? tmax : fmaxf(tmax, 0.f);   // later moves never lower the reference
-                    const float alpha = first ? 1.f : __builtin_amdgcn_exp2f(-d);
-                    M += d;
-                    l_part *= alpha;
-                    alpha_pend = alpha;
-                    pend = !first;
-#pragma unroll
-                    for (int r = 0; r < 16; r++) { Tc[r] -= d; negM[r] = -M; }
-                }
+                // (a block that still overflows after its own maximum became the reference cannot exist)
             }
-            float mx = -INFINITY;
+#endif
+            l_part += lb;
+            lb = 0.f;
             auto exp_pair = [&](int r) {                  // scores r, r+1 of the pending block
 #ifdef ABL_NOVALU
                 return;
@@ -491,14 +506,7 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
                 const bf16x2 pk = __builtin_convertvector(pv, bf16x2);
                 Pc[r / 8][r % 8] = pk[0];
                 Pc[r / 8][r % 8 + 1] = pk[1];
-                l_part = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_part, false);   // sum of what PV will use
-            };
-            auto max4 = [&](int r) {
-#ifdef ABL_NOVALU
-                return;
-#endif
-                mx = fmaxf(fmaxf(mx, Tn[r]), Tn[r + 1]);
-                mx = fmaxf(fmaxf(mx, Tn[r + 2]), Tn[r + 3]);
+                lb = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lb, false);   // sum of what PV will use
             };
             __builtin_amdgcn_sched_barrier(0);
             TRACE_MARK(0);
@@ -513,83 +521,69 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
                 Tn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[m % (PF + 1)], qreg[s2], s2 == 0 ? negM : Tn, 0, 0, 0);
                 MFMA_PRIO(0);
 #ifndef ABL_NOLOAD
-                if constexpr (s2 % (H / Gm::NI) == 0) {
-                    constexpr int li2 = s2 / (H / Gm::NI);
-                    if constexpr (i == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_k, dst_k, 16, ok.v[li2], 0, li2 * 1024, 0);
+                // all tile loads of the step go out in its first half iteration, K and V rows
+                // alternating, one every LD_SP MFMAs: they have the rest of the step to land
+                if constexpr (i == 0 && s2 % LD_SP == 0) {
+                    constexpr int q = s2 / LD_SP, li2 = q / 2;
+                    if constexpr (q % 2 == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_k, dst_k, 16, ok.v[li2], 0, li2 * 1024, 0);
                     else __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_v, dst_v, 16, ov.v[li2], 0, li2 * 1024, 0);
                 }
 #endif
-                // five score pairs over H steps (the second half also holds the row max)
-                if constexpr (H == 8) {
-                    if constexpr (s2 == 0) exp_pair(0);
-                    if constexpr (s2 == 2) exp_pair(2);
-                    if constexpr (s2 == 3) exp_pair(4);
-                    if constexpr (s2 == 5) exp_pair(6);
-                    if constexpr (s2 == 6) exp_pair(8);
-                } else {
-                    exp_pair(2 * s2);
-                    if constexpr (s2 == 3) exp_pair(8);
-                }
+                // four score pairs over H steps
+                if constexpr (H == 8) { if constexpr (s2 % 2 == 0) exp_pair(s2); }
+                else exp_pair(2 * s2);
             }, std::make_integer_sequence<int, H>{});
             static_for([&](auto sc) {
                 constexpr int s2 = decltype(sc)::value, m = m0 + s2;
                 if constexpr (m == 0) __builtin_amdgcn_sched_group_barrier(SG_DSRD, PF, 0);
                 __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
 #ifndef ABL_NOLOAD
-                if constexpr (s2 % (H / Gm::NI) == 0) __builtin_amdgcn_sched_group_barrier(SG_VMRD, 1, 0);
+                if constexpr (i == 0 && s2 % LD_SP == 0) __builtin_amdgcn_sched_group_barrier(SG_VMRD, 1, 0);
 #endif
-                __builtin_amdgcn_sched_group_barrier(SG_VALU, H == 8 ? (s2 == 1 || s2 == 4 || s2 == 7 ? 2 : 3) : 5, 0);
+                __builtin_amdgcn_sched_group_barrier(SG_VALU, 16 / H, 0);
                 if constexpr (m + PF < NM) __builtin_amdgcn_sched_group_barrier(SG_DSRD, ((m + PF) / H) & 1 ? 2 : 1, 0);
             }, std::make_integer_sequence<int, H>{});
             // the probabilities are only consumed an iteration later; keep their computation here,
             // in the MFMA shadow
             PIN_V(Pc[0]);
-            PIN_V(l_part);
+            PIN_V(lb);
             __builtin_amdgcn_sched_barrier(0);
             TRACE_MARK(1);
-            if (masked && needs_mask(j, i)) mask_block(Tn, j, i);
+#if !defined(ABL_NOBRANCH) && !defined(ABL_NOMASK)
+            if (__builtin_expect(masked, 0)) {
+                if (needs_mask(j, i)) mask_block(Tn, j, i);
+            }
+#endif
             __builtin_amdgcn_sched_barrier(0);
             TRACE_MARK(2);
             __builtin_amdgcn_sched_barrier(0);
 
-            // ---- second half: O += V^T P of block b-1  ||  keys 16-31 of block b, row max of t(b+1) ----
-            // VALU units in issue order: a score pair, the row max and the test against the
-            // reference, two score pairs -- 23 instructions dealt out over the H steps
+            // ---- second half: O += V^T P of block b-1  ||  probabilities of keys 16-31 of block b ----
             static_for([&](auto sc) {
                 constexpr int s2 = decltype(sc)::value, m = m0 + H + s2;
                 if constexpr (m + PF < NM) op[(m + PF) % (PF + 1)] = operand(IntC<m + PF>{});
                 MFMA_PRIO(1);
                 O[s2 % Gm::DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[m % (PF + 1)], Pp[s2 / Gm::DB], O[s2 % Gm::DB], 0, 0, 0);
                 MFMA_PRIO(0);
-                if constexpr (H == 8) {
-                    if constexpr (s2 == 0) exp_pair(10);
-                    if constexpr (s2 == 1) max4(0);
-                    if constexpr (s2 == 2) { max4(4); max4(8); }
-                    if constexpr (s2 == 3) max4(12);
-                    if constexpr (s2 == 4) { tmax = xmax32(mx); mv_any = __any(tmax > RESCALE_LOG2); }
-                    if constexpr (s2 == 5) exp_pair(12);
-                    if constexpr (s2 == 6) exp_pair(14);
-                } else {
-                    if constexpr (s2 == 0) { exp_pair(10); max4(0); }
-                    if constexpr (s2 == 1) { max4(4); max4(8); max4(12); }
-                    if constexpr (s2 == 2) { tmax = xmax32(mx); mv_any = __any(tmax > RESCALE_LOG2); exp_pair(12); }
-                    if constexpr (s2 == 3) exp_pair(14);
-                }
+                if constexpr (H == 8) { if constexpr (s2 % 2 == 0) exp_pair(8 + s2); }
+                else exp_pair(8 + 2 * s2);
+                // the overflow probe of this block is evaluated here, beside the last MFMA, so that the
+                // next iteration starts with a branch on a scalar that is already there
+                if constexpr (s2 == H - 1) redo = __any(!(lb <= RESCALE_SUM));
             }, std::make_integer_sequence<int, H>{});
             static_for([&](auto sc) {
                 constexpr int s2 = decltype(sc)::value, m = m0 + H + s2;
                 __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 1);
-                __builtin_amdgcn_sched_group_barrier(SG_VALU, H == 8 ? (s2 == 7 ? 2 : 3) : (s2 == 3 ? 5 : 6), 1);
+                __builtin_amdgcn_sched_group_barrier(SG_VALU, 16 / H + (s2 == H - 1 ? 1 : 0), 1);
                 if constexpr (m + PF < NM) __builtin_amdgcn_sched_group_barrier(SG_DSRD, ((m + PF) / H) & 1 ? 2 : 1, 1);
             }, std::make_integer_sequence<int, H>{});
             PIN_V(Pc[1]);
-            PIN_V(l_part);
-            PIN_V(tmax);
+            PIN_V(lb);
             __builtin_amdgcn_sched_barrier(0);
             TRACE_MARK(3);
         };
-        iteration(IntC<0>{}, T1, T0, P1, P0, false);
-        iteration(IntC<1>{}, T0, T1, P0, P1, j == 0);
+        iteration(IntC<0>{}, T1, T0, P1, P0, j == 1);      // block 0 is redone before its PV product
+        iteration(IntC<1>{}, T0, T1, P0, P1, false);
 #ifndef ABL_NOBAR
         __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0): K(j+1), V(j) are in LDS
         __syncthreads();                                  // ... and every wave is done with K(j), V(j-1)
@@ -601,12 +595,7 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
         step(j, sK0, sK1, sV1, sV0);
         if (j + 1 <= n_tiles) step(j + 1, sK1, sK0, sV0, sV1);
     }
-    if (pend) {
-#pragma unroll
-        for (int db = 0; db < Gm::DB; db++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) O[db][r] *= alpha_pend;
-    }
+    l_part += lb;                                          // the drained blocks are fully masked: lb is 0
 
 #ifdef PBKV_TRACE
     if (p.trace && l == 0 && w == 0 && blockIdx.x < 4096) {

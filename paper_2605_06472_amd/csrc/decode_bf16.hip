@@ -29,7 +29,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 constexpr int DEC_WAVES = 4;
-constexpr float DEC_RESCALE_LOG2 = 8.0f;
+[[maybe_unused]] constexpr float DEC_RESCALE_LOG2 = 8.0f;
 
 int decode_heads_per_group(int group) { return group < 8 ? group : 8; }
 
