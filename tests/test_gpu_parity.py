@@ -282,3 +282,30 @@ def test_swap_out_bit_exact_and_round_trip(oracle):
     assert e.value.code == -4
     # empty list is a no-op
     binding.swap_out_pages(db.shape, db.kv_pool, np.zeros(0, np.int32), host)
+
+
+@pytest.mark.parametrize("slope", [0.05, -0.05], ids=["rising", "falling"])
+def test_scores_that_run_away_along_the_context(oracle, slope):
+    """Scores that climb (or fall) by ~100 log2 units per 32-key block: every block overflows the
+    reference set by its predecessors (or underflows it), so the kernel's redo path runs at every
+    block; the result must still match the exact definition."""
+    b = W.ragged_small(95, "bf16", prefix_lens=(300, 37, 0), new_lens=(70, 5, 40), num_pages=64)
+    d = b.d
+    u = np.sign(np.random.default_rng(3).standard_normal(d)).astype(np.float32)       # |u|^2 = d
+    q = np.broadcast_to(4.0 * u, W.to_f64(b.q).shape).astype(np.float32)
+    b.q = W.f32_to_bf16_bits(q)
+    # key t of a request = u * slope * (t + 1): prefix keys live in the pool, suffix keys in k_new
+    off = 0
+    for r in range(b.B):
+        p, n = int(b.prefix_lens[r]), int(b.new_lens[r])
+        t = np.arange(p + n, dtype=np.float32) + 1.0
+        keys = W.f32_to_bf16_bits((slope * t)[:, None, None] * np.broadcast_to(u, (p + n, b.Hkv, d)))
+        for tok in range(p):
+            b.kv_pool[b.block_table[r, tok // b.P], 0, :, tok % b.P] = keys[tok]
+        b.k_new[off:off + n] = keys[p:]
+        off += n
+    db = DeviceBatch(b)
+    db.prefill()
+    torch.cuda.synchronize()
+    want = _oracle(oracle, b)
+    assert_close(db.out_f64(), want, "bf16", "runaway scores, slope %g" % slope)
