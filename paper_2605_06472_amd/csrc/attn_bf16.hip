@@ -158,6 +158,9 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
     constexpr int H = Gm::H;
     constexpr int NT = 64 * NW;
     constexpr int ROWB = Gm::ROWB;
+#ifdef PBKV_TRACE
+    const unsigned long long tr_entry = __builtin_amdgcn_s_memrealtime();
+#endif
 
     // four separate arrays: the direct-to-LDS loads of one buffer provably do not alias
     // the operand reads of the others
@@ -494,6 +497,9 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
                 // (a block that still overflows after its own maximum became the reference cannot exist)
             }
 #endif
+#ifdef ABL_NOBRANCH
+            asm volatile("" : "+v"(negM));                // the reference may have moved: no hoisting of the score product
+#endif
             l_part += lb;
             lb = 0.f;
             auto exp_pair = [&](int r) {                  // scores r, r+1 of the pending block
@@ -599,9 +605,10 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
 
 #ifdef PBKV_TRACE
     if (p.trace && l == 0 && w == 0 && blockIdx.x < 4096) {
-        unsigned long long *sp = (unsigned long long *)p.trace + 64 * 8 * 8 + blockIdx.x * 2;
-        sp[0] = tr_r0;
-        sp[1] = __builtin_amdgcn_s_memrealtime();
+        unsigned long long *sp = (unsigned long long *)p.trace + 64 * 8 * 8 + blockIdx.x * 4;
+        sp[0] = tr_entry;
+        sp[1] = tr_r0;
+        sp[2] = __builtin_amdgcn_s_memrealtime();
     }
     if (p.trace && l == 0 && blockIdx.x < 64) {
         unsigned long long *tp = (unsigned long long *)p.trace + (blockIdx.x * NW + w) * 8;
@@ -626,6 +633,10 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
                 *(bf16x4 *)(op + 16 * db + 8 * (b4 & 1) + (D / 2) * (b4 >> 1)) = v;
             }
     }
+#ifdef PBKV_TRACE
+    if (p.trace && l == 0 && w == 0 && blockIdx.x < 2048)
+        ((unsigned long long *)p.trace)[64 * 8 * 8 + blockIdx.x * 4 + 3] = __builtin_amdgcn_s_memrealtime();
+#endif
     }   // !PROBE
 #endif
 }
@@ -646,11 +657,11 @@ static void trace_dump(void *dev, int nw) {
     hipMemcpy(h, dev, sizeof h, hipMemcpyDeviceToHost);
     {
         unsigned long long *sp = h + 64 * 8 * 8, t0 = ~0ull, t1 = 0; int nb = 0;
-        for (int b = 0; b < 4096; b++) if (sp[2 * b]) { nb++; if (sp[2 * b] < t0) t0 = sp[2 * b]; if (sp[2 * b + 1] > t1) t1 = sp[2 * b + 1]; }
-        int late = 0; double sum_life = 0;
-        for (int b = 0; b < 4096; b++) if (sp[2 * b]) { if (sp[2 * b] - t0 > 2000) late++; sum_life += sp[2 * b + 1] - sp[2 * b]; }
-        printf("trace: %d blocks, span %.1f us, mean block life %.1f us, blocks starting >20us late: %d\n", nb, (t1 - t0) / 100.0, sum_life / nb / 100.0, late);
-        for (int b = 0; b < nb; b += nb / 16) printf("  block %d start %.1f end %.1f\n", b, (sp[2 * b] - t0) / 100.0, (sp[2 * b + 1] - t0) / 100.0);
+        for (int b = 0; b < 2048; b++) if (sp[4 * b]) { nb++; if (sp[4 * b] < t0) t0 = sp[4 * b]; if (sp[4 * b + 3] > t1) t1 = sp[4 * b + 3]; }
+        double pro = 0, loop = 0, epi = 0, first = 0;
+        for (int b = 0; b < 2048; b++) if (sp[4 * b]) { first += sp[4 * b] - t0; pro += sp[4 * b + 1] - sp[4 * b]; loop += sp[4 * b + 2] - sp[4 * b + 1]; epi += sp[4 * b + 3] - sp[4 * b + 2]; }
+        printf("trace: %d blocks, span %.2f us; mean entry delay %.2f us, prologue %.2f us, loop %.2f us, epilogue %.2f us\n", nb, (t1 - t0) / 100.0, first / nb / 100.0, pro / nb / 100.0, loop / nb / 100.0, epi / nb / 100.0);
+        for (int b = 0; b < nb; b += nb / 16) printf("  block %d entry %.2f loop %.2f..%.2f exit %.2f\n", b, (sp[4 * b] - t0) / 100.0, (sp[4 * b + 1] - t0) / 100.0, (sp[4 * b + 2] - t0) / 100.0, (sp[4 * b + 3] - t0) / 100.0);
     }
     const char *names[6] = {"top", "half1", "mask", "half2", "barrier", "carry"};
     for (int b = 0; b < 64; b += 21)

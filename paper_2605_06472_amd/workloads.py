@@ -367,6 +367,90 @@ def decode_batch(seed: int = 1005, batch: int = 64, min_ctx: int = 1024, max_ctx
                      [[_seg(c)] for c in ctx], [1] * batch, q_scale=q_scale)
 
 
+# ----------------------------------------------------------------------------
+# workflow predictor (App. B): random-init model of the stated widths and a batch of workflow states
+# ----------------------------------------------------------------------------
+@dataclasses.dataclass
+class PredictorModel:
+    """Weights of the predictor, all float32, row-major, named as in App. B.  The paper gives the
+    parameter count (~350 K) and the served model (Qwen3-32B, hidden width 5120) but not the
+    widths; V=8, d=64, hidden=64, K=3 with a 5120-wide x give 362 779 parameters."""
+    V: int
+    d: int
+    d_x: int
+    hidden: int
+    K: int
+    emb: np.ndarray        # H^(0)  [V][d]
+    trans: np.ndarray      # A      [V][V], rows sum to 1 (or are all zero: an agent never left)
+    w1: np.ndarray         # W^(1)  [d][2d]
+    w2: np.ndarray         # W^(2)  [d][2d]
+    wq: np.ndarray         # W_q    [d][d]
+    wt: np.ndarray         # W_t    [d][d_x]
+    wa: np.ndarray         # first MLP layer  [hidden][3d]   (input order: h_cur, h_path, h_txt)
+    ba: np.ndarray         # [hidden]
+    wb: np.ndarray         # second MLP layer [K*(V+1)][hidden], output index = k*(V+1) + agent, END last
+    bb: np.ndarray         # [K*(V+1)]
+
+    def num_params(self) -> int:
+        return sum(int(getattr(self, n).size) for n in ("emb", "w1", "w2", "wq", "wt", "wa", "ba", "wb", "bb"))
+
+
+@dataclasses.dataclass
+class PredictorBatch:
+    B: int
+    L: int                 # prefix slots per request
+    x: np.ndarray          # [B][d_x] bf16 bit patterns: post-norm hidden state of the last prefill token
+    cur_agent: np.ndarray  # [B] int32: v_t
+    prefix: np.ndarray     # [B][L] int32: v_1 .. v_{t-1} in the first prefix_len slots (rest: -1)
+    prefix_len: np.ndarray  # [B] int32: t - 1 in [0, L]
+
+
+def predictor_model(seed: int = 2000, V: int = 8, d: int = 64, d_x: int = 5120, hidden: int = 64,
+                    K: int = 3, gain: float = 1.0) -> PredictorModel:
+    """Random-init weights (N(0, gain^2 / fan_in), embeddings N(0, 1)) and a looped call graph:
+    every agent has 1-3 successors with random counts, as a transition matrix estimated from
+    traces would look (Sec. 2, App. B)."""
+    rng = np.random.Generator(np.random.Philox(np.random.SeedSequence([seed, 31])))
+
+    def w(rows, cols, fan_in):
+        return (rng.standard_normal((rows, cols)) * gain / np.sqrt(fan_in)).astype(np.float32)
+
+    counts = np.zeros((V, V))
+    for v in range(V):
+        succ = rng.choice(V, size=int(rng.integers(1, min(3, V) + 1)), replace=False)
+        counts[v, succ] = rng.integers(1, 20, size=len(succ))
+    trans = (counts / counts.sum(1, keepdims=True)).astype(np.float32)
+    return PredictorModel(V, d, d_x, hidden, K,
+                          emb=rng.standard_normal((V, d)).astype(np.float32), trans=trans,
+                          w1=w(d, 2 * d, 2 * d), w2=w(d, 2 * d, 2 * d), wq=w(d, d, d), wt=w(d, d_x, d_x),
+                          wa=w(hidden, 3 * d, 3 * d), ba=(rng.standard_normal(hidden) * 0.1).astype(np.float32),
+                          wb=w(K * (V + 1), hidden, hidden),
+                          bb=(rng.standard_normal(K * (V + 1)) * 0.1).astype(np.float32))
+
+
+def predictor_batch(model: PredictorModel, seed: int = 2001, B: int = 1024, L: int = 16,
+                    sigma_x: float = 1.0) -> PredictorBatch:
+    """B workflow states: a walk of U{1..L+1} invocations over the model's call graph (the last
+    one is the current agent, the ones before it the prefix) and an N(0, sigma_x^2) hidden state."""
+    rng = np.random.Generator(np.random.Philox(np.random.SeedSequence([seed, 37])))
+    cur = np.zeros(B, np.int32)
+    prefix = np.full((B, L), -1, np.int32)
+    plen = np.zeros(B, np.int32)
+    for b in range(B):
+        t = int(rng.integers(1, L + 2))
+        v = int(rng.integers(model.V))
+        walk = [v]
+        for _ in range(t - 1):
+            row = model.trans[v].astype(np.float64)
+            v = int(rng.choice(model.V, p=row / row.sum())) if row.sum() > 0 else int(rng.integers(model.V))
+            walk.append(v)
+        cur[b] = walk[-1]
+        plen[b] = t - 1
+        prefix[b, :t - 1] = walk[:-1]
+    x = normal_tensor(seed, 41, (B, model.d_x), sigma_x, "bf16")
+    return PredictorBatch(B, L, x, cur, prefix, plen)
+
+
 CONFIGS = {
     "cfg0": tiny_fp32,
     "cfg1": shared_system_prompt,
