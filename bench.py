@@ -365,6 +365,63 @@ def gather_rate(db, torch, binding, reps=5):
             "gather_distinct_frac_of_hbm_peak_cold": distinct / cold / 1e9 / PEAK_HBM_GBS}
 
 
+def predictor_rate(torch, W, reps=2000, n_x=32):
+    """Forward pass of the workflow predictor (App. B) on a batch of 1024 workflow states, the
+    batch the paper quotes its latency on (Sec. 4.1).  The hidden states rotate over n_x buffers
+    (336 MB, more than the 256 MB of Infinity Cache) so that x comes from HBM as it would after a
+    prefill.  Algorithmic bytes per batch = x + indices + probabilities + the prepared weights once."""
+    from paper_2605_06472_amd import predictor as PR
+    from tests.gpu_util import to_torch
+    m = W.predictor_model()
+    L, B = 16, 1024
+    b = W.predictor_batch(m, B=B, L=L)
+    shape = PR.make_shape(m.V, m.d, m.d_x, m.hidden, m.K, L)
+    nbytes = PR.predictor_workspace_bytes(shape, B)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    weights = {n: to_torch(np.ascontiguousarray(getattr(m, n))) for n in PR.WEIGHT_NAMES}
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    PR.predictor_prepare(shape, weights, ws, nbytes, B)
+    e1.record()
+    torch.cuda.synchronize()
+    prepare_ms = e0.elapsed_time(e1)
+    xs = [to_torch(b.x) for _ in range(n_x)]
+    cur, pre, plen = to_torch(b.cur_agent), to_torch(b.prefix), to_torch(b.prefix_len)
+    probs = torch.empty((B, m.K, m.V + 1), dtype=torch.float32, device="cuda")
+    for i in range(300):                             # long enough for the clocks to come up
+        PR.predictor_forward(shape, ws, nbytes, B, xs[i % n_x], cur, pre, plen, B, probs)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(reps):
+        PR.predictor_forward(shape, ws, nbytes, B, xs[i % n_x], cur, pre, plen, B, probs)
+    e1.record()
+    torch.cuda.synchronize()
+    t = e0.elapsed_time(e1) * 1e-3 / reps
+    # same buffer every time: x served by the caches
+    e0.record()
+    for i in range(reps):
+        PR.predictor_forward(shape, ws, nbytes, B, xs[0], cur, pre, plen, B, probs)
+    e1.record()
+    torch.cuda.synchronize()
+    t_warm = e0.elapsed_time(e1) * 1e-3 / reps
+    from oracle import predictor_oracle
+    t0 = time.perf_counter()
+    want = predictor_oracle.forward(m, b.x, b.cur_agent, b.prefix, b.prefix_len)
+    ref_ms = (time.perf_counter() - t0) * 1e3
+    err = float(np.abs(probs.cpu().numpy().astype(np.float64) - want).max())
+    alg = B * m.d_x * 2 + B * (L + 2) * 4 + B * m.K * (m.V + 1) * 4 + 2 * m.d * m.d_x * 2 + (m.V * m.d + m.V * m.V + 3 * m.d * m.hidden + m.hidden * (m.K * (m.V + 1) + 1) + m.K * (m.V + 1)) * 4
+    flops = 2 * 2 * B * m.d * m.d_x + 2 * B * (3 * m.d * m.hidden + m.hidden * m.K * (m.V + 1))
+    return {"workload": "predictor forward: %d requests, |V|=%d, d=%d, d_x=%d, hidden=%d, K=%d, %d parameters"
+                        % (B, m.V, m.d, m.d_x, m.hidden, m.K, m.num_params()),
+            "batch_ms": t * 1e3, "batch_ms_x_cached": t_warm * 1e3, "requests_per_s": B / t, "prepare_ms": prepare_ms,
+            "max_abs_err_vs_reference": err, "reference_model_ms": ref_ms,
+            "roofline": {"bound": "hbm", "achieved": alg / t / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": alg / t / 1e9 / PEAK_HBM_GBS, "algorithmic_bytes": alg},
+            "mfma_tflops": flops / t / 1e12,
+            "paper_context_ms": {"PredictInfer_batch_1024": 1.56,
+                                 "note": "Sec. 4.1: the paper's predictor (PyTorch, its GPUs), same batch size; widths are not published"}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -372,7 +429,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", default="cfg1", choices=["cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads and the CPU baseline")
-    ap.add_argument("--part", default=None, choices=["decode", "policy"],
+    ap.add_argument("--part", default=None, choices=["decode", "policy", "predictor"],
                     help="run only this secondary measurement and print its JSON object (for profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 256 MiB device-to-device copies (known HBM traffic) so that a "
@@ -407,6 +464,9 @@ def main():
         return
     if args.part == "policy":
         print(json.dumps(policy_latency()))
+        return
+    if args.part == "predictor":
+        print(json.dumps(predictor_rate(torch, W)))
         return
 
     b, db, wall, kern_ms = time_config(args.config, args.steps, args.warmup, torch, binding, W, DeviceBatch)
@@ -497,6 +557,10 @@ def main():
             extra["policy"] = policy_latency()
         except Exception as e:
             extra["policy"] = {"error": repr(e)}
+        try:
+            extra["predictor"] = predictor_rate(torch, W)
+        except Exception as e:
+            extra["predictor"] = {"error": repr(e)}
         line["extra"] = extra
 
     print(json.dumps(line))

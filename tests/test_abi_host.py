@@ -110,3 +110,49 @@ def test_pointer_kind_is_checked_before_any_launch():
     with pytest.raises(binding.PbkvError) as e:
         binding.swap_in_pages(_shape(), addr, np.array([3], np.int32), FAKE, stream=0)
     assert e.value.code == -6
+
+
+# ---- predictor boundary (pbkv_predictor.h): host-side validation -------------------------------
+def test_predictor_workspace_size_and_bad_shapes():
+    from paper_2605_06472_amd import predictor as PR
+    good = PR.make_shape(8, 64, 5120, 64, 3, 16)
+    n = PR.predictor_workspace_bytes(good, 1024)
+    # W_t twice in bf16 + the partial sums of 16 slices dominate
+    assert n >= 2 * 64 * 5120 * 2 + 16 * 1024 * 64 * 4 and n % 256 == 0
+    assert PR.predictor_workspace_bytes(good, 1) < n
+    for bad in [PR.make_shape(0, 64, 5120, 64, 3, 16), PR.make_shape(65, 64, 5120, 64, 3, 16),
+                PR.make_shape(8, 48, 5120, 64, 3, 16), PR.make_shape(8, 64, 5000, 64, 3, 16),
+                PR.make_shape(8, 64, 32, 64, 3, 16), PR.make_shape(8, 64, 5120, 0, 3, 16),
+                PR.make_shape(8, 64, 5120, 257, 3, 16), PR.make_shape(8, 64, 5120, 64, 9, 16),
+                PR.make_shape(8, 64, 5120, 64, 3, 65)]:
+        with pytest.raises(binding.PbkvError) as e:
+            PR.predictor_workspace_bytes(bad, 16)
+        assert e.value.code == -2 and str(e.value)
+    with pytest.raises(binding.PbkvError) as e:
+        PR.predictor_workspace_bytes(good, 0)
+    assert e.value.code == -4
+
+
+def test_predictor_calls_reject_bad_arguments_on_the_host():
+    from paper_2605_06472_amd import predictor as PR
+    good = PR.make_shape(8, 64, 5120, 64, 3, 16)
+    n = PR.predictor_workspace_bytes(good, 64)
+    w = {k: FAKE for k in PR.WEIGHT_NAMES}
+    with pytest.raises(binding.PbkvError) as e:
+        PR.predictor_prepare(good, w, FAKE, n - 1, 64, stream=0)            # workspace too small
+    assert e.value.code == -4
+    with pytest.raises(binding.PbkvError) as e:
+        PR.predictor_prepare(good, w, None, n, 64, stream=0)
+    assert e.value.code == -1
+    with pytest.raises(binding.PbkvError) as e:
+        PR.predictor_prepare(good, w, FAKE + 16, n, 64, stream=0)           # not 256-byte aligned
+    assert e.value.code == -2
+    with pytest.raises(binding.PbkvError) as e:
+        PR.predictor_forward(good, FAKE, n, 64, FAKE, FAKE, FAKE, FAKE, 65, FAKE, stream=0)   # batch > max_batch
+    assert e.value.code == -4
+    with pytest.raises(binding.PbkvError) as e:
+        PR.predictor_forward(good, FAKE, n, 64, FAKE, FAKE, FAKE, FAKE, -1, FAKE, stream=0)
+    assert e.value.code == -4
+    with pytest.raises(binding.PbkvError) as e:
+        PR.predictor_forward(PR.make_shape(8, 64, 5120, 64, 3, 99), FAKE, n, 64, FAKE, FAKE, FAKE, FAKE, 1, FAKE, stream=0)
+    assert e.value.code == -2
