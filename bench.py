@@ -83,7 +83,7 @@ class Step:
         self.main.wait_event(self.join_ev)
 
 
-def time_config(name, steps, warmup, torch, binding, W, DeviceBatch):
+def time_config(name, steps, warmup, torch, binding, W, DeviceBatch, events=True):
     b = W.CONFIGS[name]()
     db = DeviceBatch(b)
     if b.host_pages is not None:            # make every prefix page resident before timing attention
@@ -93,7 +93,10 @@ def time_config(name, steps, warmup, torch, binding, W, DeviceBatch):
         st.run()
     st.join()
     torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    # every attention launch of the timed region is bracketed by HIP events (events=False: none is; the
+    # two event packets per step cost ~6 % of a cfg1 step, reported apart as a second measurement)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) if events else (None, None)
+           for k in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(steps):
@@ -101,7 +104,7 @@ def time_config(name, steps, warmup, torch, binding, W, DeviceBatch):
     st.join()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    kern_ms = float(np.mean([a.elapsed_time(c) for a, c in evs]))
+    kern_ms = float(np.mean([a.elapsed_time(c) for a, c in evs])) if events else None
     return b, db, wall, kern_ms
 
 
@@ -514,6 +517,13 @@ def main():
                                 "sample": "%d of %d suffix rows (evenly spaced, all %d query heads) of %s, %.1f s"
                                           % (len(rows), b.N, b.Hq, b.name, dt)}
         extra = {}
+        try:
+            _, dbn, walln, _ = time_config(args.config, args.steps, args.warmup, torch, binding, W, DeviceBatch, events=False)
+            extra["same_steps_without_event_packets"] = {"ms_per_step": walln / args.steps * 1e3,
+                                                         "new_tokens_per_s": b.N / (walln / args.steps)}
+            del dbn
+        except Exception as e:
+            extra["same_steps_without_event_packets"] = {"error": repr(e)}
         for name in ("cfg2", "cfg3", "cfg4"):
             if name == args.config:
                 continue
