@@ -160,3 +160,48 @@ def test_policy_decisions_drive_the_page_movers_and_attention(oracle):
     # the retired branch of workflow 200 is what the next eviction takes, before any active node
     evicted, freed = pol.evict(1, to_host=False)
     assert evicted == [20] and freed == 4
+
+
+def test_predictor_output_drives_the_policy_decisions():
+    """Predictor -> policy: the GPU forward pass' distributions are the forecasts of the policy core.
+    The scores it then reports equal Eq. 2 evaluated on the fp64 reference's distributions, and its
+    eviction order is the reference policy model's order under the same forecasts."""
+    from oracle import policy_oracle, predictor_oracle
+    from paper_2605_06472_amd import predictor as PR
+    V, K, gamma = 4, 3, 0.7
+    m = W.predictor_model(501, V=V, d=32, d_x=256, hidden=24, K=K, gain=2.0)
+    b = W.predictor_batch(m, seed=502, B=6, L=5)
+    shape = PR.make_shape(V, m.d, m.d_x, m.hidden, K, 5)
+    nbytes = PR.predictor_workspace_bytes(shape, 8)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    PR.predictor_prepare(shape, {n: to_torch(np.ascontiguousarray(getattr(m, n))) for n in PR.WEIGHT_NAMES}, ws, nbytes, 8)
+    probs_dev = torch.empty((6, K, V + 1), dtype=torch.float32, device="cuda")
+    PR.predictor_forward(shape, ws, nbytes, 8, to_torch(b.x), to_torch(b.cur_agent), to_torch(b.prefix),
+                         to_torch(b.prefix_len), 6, probs_dev)
+    torch.cuda.synchronize()
+    probs = probs_dev.cpu().numpy().astype(np.float64)
+    want = predictor_oracle.forward(m, b.x, b.cur_agent, b.prefix, b.prefix_len)
+    assert np.abs(probs - want).max() < 1e-5
+
+    pol = PC.Policy(num_agents=V, horizon=K, gamma=gamma)
+    ref = policy_oracle.PolicyOracle(V, K, gamma)
+    # one shared root, one private node per workflow; workflow w was last served by agent w % V
+    for p_ in (pol, ref):
+        p_.node_add(0, -1, 4)
+        for wf in range(6):
+            p_.node_add(10 + wf, 0, 2 + wf % 3)
+        for wf in range(6):
+            p_.access(wf, wf % V, [0, 10 + wf])
+            p_.forecast(wf, probs[wf])
+    for wf in range(6):
+        a = wf % V
+        surv, score = 1.0, 0.0
+        for k in range(K):                                   # Eq. 2 on the reference's distributions
+            score += gamma ** k * surv * want[wf, k, a]
+            surv *= 1.0 - want[wf, k, V]
+        assert abs(pol.score(10 + wf) - score) < 1e-5
+        assert abs(pol.score(10 + wf) - ref.score(10 + wf)) < 1e-12
+    got, freed = pol.evict(9, to_host=True)
+    exp, freed_ref = ref.evict(9, to_host=True)
+    assert got == exp and freed == freed_ref and len(got) >= 3
+    assert 0 not in got                                      # the shared root has GPU-resident children
