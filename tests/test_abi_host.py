@@ -156,3 +156,14 @@ def test_predictor_calls_reject_bad_arguments_on_the_host():
     with pytest.raises(binding.PbkvError) as e:
         PR.predictor_forward(PR.make_shape(8, 64, 5120, 64, 3, 99), FAKE, n, 64, FAKE, FAKE, FAKE, FAKE, 1, FAKE, stream=0)
     assert e.value.code == -2
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU; asking bench.py for more ends with a message and a non-zero status
+    before anything touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
+    assert r.stdout.strip() == ""
