@@ -103,19 +103,34 @@ static __device__ __forceinline__ void static_for(F &&f, std::integer_sequence<i
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// Waves per work-group: 8 (two waves per SIMD share one set of K/V tiles; default) or 4
-// (two work-groups per CU).
-static int launch_waves() {
-    static int v = [] {
+// Waves per work-group: 8 (one work-group per CU, its two waves per SIMD share one set of K/V
+// tiles) or 4 (two work-groups per CU, each staging its own tiles).  Eight waves stage every tile
+// once and win when work-groups are long; four overlap one work-group's prologue and epilogue
+// (three dependent fetches before the first tile step, the output stores after the last) with the
+// other's arithmetic and cut the work twice as fine, which wins when work-groups are short or few:
+// measured +3 % / +5 % / 0 / -5 % on launches whose 64-token blocks average 37 / 70 / 152 / 513
+// tile steps.  PBKV_ATTN_WAVES=4|8 overrides the choice.
+int attn_bf16_waves(const int32_t *prefix_lens, const int32_t *new_lens, int batch) {
+    static const int forced = [] {
         const char *e = getenv("PBKV_ATTN_WAVES");
-        return (e && atoi(e) == 4) ? 4 : 8;
+        const int v = e ? atoi(e) : 0;
+        return v == 4 || v == 8 ? v : 0;
     }();
-    return v;
+    if (forced) return forced;
+    int64_t steps = 0, blocks = 0;
+    for (int r = 0; r < batch; r++) {
+        const int64_t tp = (prefix_lens[r] + BN - 1) / BN;
+        for (int t0 = 0; t0 < new_lens[r]; t0 += 64) {
+            steps += tp + (std::min(t0 + 64, new_lens[r]) + BN - 1) / BN + 1;
+            blocks++;
+        }
+    }
+    return blocks > 0 && steps < 128 * blocks ? 4 : 8;
 }
 
-int attn_bf16_tile_tokens(int /*head_dim*/, int group) {
+int attn_bf16_tile_tokens(int /*head_dim*/, int group, int waves) {
     const int gw = group < 4 ? group : 4;
-    return 32 * (launch_waves() / gw);
+    return 32 * (waves / gw);
 }
 
 // Keeps a value (and so the code that computes it) at this point of the program; the
@@ -681,12 +696,12 @@ hipError_t launch_attn_bf16(const AttnParams &p0, int head_dim, hipStream_t s) {
     static void *trace_buf = nullptr;
     if (!trace_buf) { hipMalloc(&trace_buf, (64 * 8 * 8 + 8192) * 8); hipMemset(trace_buf, 0, (64 * 8 * 8 + 8192) * 8); }
     p.trace = trace_buf;
-    struct Dump { void *b; int nw; ~Dump() { trace_dump(b, nw); } } dump{trace_buf, launch_waves()};
+    struct Dump { void *b; int nw; ~Dump() { trace_dump(b, nw); } } dump{trace_buf, p.waves};
 #endif
     if (p.n_tiles == 0) return hipSuccess;
     const int G = p.Hq / p.Hkv;
     const int Gw = G < 4 ? G : 4;
-    if (launch_waves() == 4) return head_dim == 128 ? launch_one<128, 4, false>(p, G, Gw, s) : launch_one<64, 4, false>(p, G, Gw, s);
+    if (p.waves == 4) return head_dim == 128 ? launch_one<128, 4, false>(p, G, Gw, s) : launch_one<64, 4, false>(p, G, Gw, s);
     return head_dim == 128 ? launch_one<128, 8, false>(p, G, Gw, s) : launch_one<64, 8, false>(p, G, Gw, s);
 }
 
@@ -699,7 +714,7 @@ hipError_t launch_gather_probe(const AttnParams &p, int head_dim, hipStream_t s)
     if (p.n_tiles == 0) return hipSuccess;
     const int G = p.Hq / p.Hkv;
     const int Gw = G < 4 ? G : 4;
-    if (launch_waves() == 4) return head_dim == 128 ? launch_one<128, 4, true>(p, G, Gw, s) : launch_one<64, 4, true>(p, G, Gw, s);
+    if (p.waves == 4) return head_dim == 128 ? launch_one<128, 4, true>(p, G, Gw, s) : launch_one<64, 4, true>(p, G, Gw, s);
     return head_dim == 128 ? launch_one<128, 8, true>(p, G, Gw, s) : launch_one<64, 8, true>(p, G, Gw, s);
 }
 

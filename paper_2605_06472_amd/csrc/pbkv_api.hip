@@ -300,7 +300,8 @@ int pbkv_prefix_prefill(const pbkv_shape *s, const void *q, const void *k_new, c
         return rc;
 
     const int G = s->num_q_heads / s->num_kv_heads;
-    const int T = s->dtype == PBKV_BF16 ? pbkv::attn_bf16_tile_tokens(s->head_dim, G) : pbkv::attn_f32_tile_tokens();
+    const int waves = s->dtype == PBKV_BF16 ? pbkv::attn_bf16_waves(prefix_lens, new_lens, s->batch) : 0;
+    const int T = s->dtype == PBKV_BF16 ? pbkv::attn_bf16_tile_tokens(s->head_dim, G, waves) : pbkv::attn_f32_tile_tokens();
     std::vector<pbkv::TileDesc> tiles;
     if ((rc = build_tiles(s, prefix_lens, new_lens, T, &tiles))) return rc;
 
@@ -315,6 +316,7 @@ int pbkv_prefix_prefill(const pbkv_shape *s, const void *q, const void *k_new, c
     p.n_tiles = (int32_t)tiles.size();
     p.Hq = s->num_q_heads; p.Hkv = s->num_kv_heads;
     p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
+    p.waves = waves;
     p.trace = nullptr;
     hipStream_t st = (hipStream_t)stream;
     if ((rc = ring_commit(lease, tiles.size() * sizeof(pbkv::TileDesc), st))) return rc;
@@ -335,14 +337,16 @@ int pbkv_gather_probe(const pbkv_shape *s, const void *k_new, const void *v_new,
     if (s->dtype != PBKV_BF16) return fail(PBKV_ERR_DTYPE, "pbkv_gather_probe: bf16 only");
     if (!n_units || !unit_tokens) return fail(PBKV_ERR_NULL, "pbkv_gather_probe: NULL argument");
     const int G = s->num_q_heads / s->num_kv_heads;
-    const int T = pbkv::attn_bf16_tile_tokens(s->head_dim, G);
-    *unit_tokens = T;
+    *unit_tokens = pbkv::attn_bf16_tile_tokens(s->head_dim, G, 8);
     *n_units = 0;
     if (s->batch == 0) return PBKV_OK;
     if (!k_new || !v_new || !kv_pool || !block_table || !prefix_lens || !new_lens)
         return fail(PBKV_ERR_NULL, "pbkv_gather_probe: NULL argument");
     int64_t N = 0;
     if ((rc = check_lens(s, prefix_lens, new_lens, &N))) return rc;
+    const int waves = pbkv::attn_bf16_waves(prefix_lens, new_lens, s->batch);   // the attention call's own choice
+    const int T = pbkv::attn_bf16_tile_tokens(s->head_dim, G, waves);
+    *unit_tokens = T;
     std::vector<pbkv::TileDesc> tiles;
     if ((rc = build_tiles(s, prefix_lens, new_lens, T, &tiles))) return rc;
     const int64_t units = (int64_t)tiles.size() * pbkv::attn_bf16_units_per_tile(s->num_kv_heads, G);
@@ -370,6 +374,7 @@ int pbkv_gather_probe(const pbkv_shape *s, const void *k_new, const void *v_new,
     p.n_tiles = (int32_t)tiles.size();
     p.Hq = s->num_q_heads; p.Hkv = s->num_kv_heads;
     p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
+    p.waves = waves;
     p.trace = nullptr;
     hipStream_t st = (hipStream_t)stream;
     if ((rc = ring_commit(lease, tiles.size() * sizeof(pbkv::TileDesc), st))) return rc;

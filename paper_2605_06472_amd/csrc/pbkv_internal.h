@@ -39,6 +39,7 @@ struct AttnParams {
     const int32_t *block_table;
     const TileDesc *tiles;
     int32_t n_tiles, Hq, Hkv, max_pages, num_pages;
+    int32_t waves;   // bf16 kernel: waves per work-group (attn_bf16_waves); the tiles were cut for it
     void *trace;   // development instrumentation; unused unless built with it
 };
 
@@ -76,8 +77,10 @@ struct AppendParams {
     int32_t n_descs, Hkv, max_pages, num_pages;
 };
 
-// Tokens per attention tile for a shape (what the host cuts the suffix into).
-int attn_bf16_tile_tokens(int head_dim, int group);
+// Waves per work-group the bf16 kernel runs this batch with, and the tokens per attention tile
+// that follow from it (what the host cuts the suffix into).
+int attn_bf16_waves(const int32_t *prefix_lens, const int32_t *new_lens, int batch);
+int attn_bf16_tile_tokens(int head_dim, int group, int waves);
 int attn_f32_tile_tokens();
 
 // Launchers: all arguments already validated.  Return the hipError of the launch.
