@@ -111,12 +111,9 @@ static __device__ __forceinline__ void static_for(F &&f, std::integer_sequence<i
 // measured +3 % / +5 % / 0 / -5 % on launches whose 64-token blocks average 37 / 70 / 152 / 513
 // tile steps.  PBKV_ATTN_WAVES=4|8 overrides the choice.
 int attn_bf16_waves(const int32_t *prefix_lens, const int32_t *new_lens, int batch) {
-    static const int forced = [] {
-        const char *e = getenv("PBKV_ATTN_WAVES");
-        const int v = e ? atoi(e) : 0;
-        return v == 4 || v == 8 ? v : 0;
-    }();
-    if (forced) return forced;
+    const char *e = getenv("PBKV_ATTN_WAVES");            // read on every call: tests switch it
+    const int forced = e ? atoi(e) : 0;
+    if (forced == 4 || forced == 8) return forced;
     int64_t steps = 0, blocks = 0;
     for (int r = 0; r < batch; r++) {
         const int64_t tp = (prefix_lens[r] + BN - 1) / BN;

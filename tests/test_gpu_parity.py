@@ -71,6 +71,29 @@ def test_ragged_small_batches(oracle, name):
     _check_full(oracle, b, name)
 
 
+@pytest.mark.parametrize("waves", ["4", "8"])
+@pytest.mark.parametrize("name", sorted(n for n in RAGGED if n.startswith("bf16")))
+def test_both_work_group_shapes_of_the_bf16_kernel(oracle, name, waves, monkeypatch):
+    """The library picks the work-group shape (4 or 8 waves) from the batch; small batches like these
+    would only ever see one of them, so both are forced in turn."""
+    monkeypatch.setenv("PBKV_ATTN_WAVES", waves)
+    b = W.ragged_small(40, **RAGGED[name])
+    _check_full(oracle, b, "%s, %s waves" % (name, waves))
+
+
+def test_the_work_group_shape_does_not_change_a_bit(monkeypatch):
+    """A row is computed by one wave in the same order of operations whichever shape the launch has."""
+    b = W.ragged_small(41, "bf16", prefix_lens=(300, 77, 1000, 0), new_lens=(200, 65, 130, 257), num_pages=256, q_scale=8.0)
+    outs = []
+    for waves in ("4", "8"):
+        monkeypatch.setenv("PBKV_ATTN_WAVES", waves)
+        db = DeviceBatch(b)
+        db.prefill()
+        torch.cuda.synchronize()
+        outs.append(to_numpy(db.out))
+    assert np.array_equal(outs[0], outs[1])
+
+
 def test_single_row_and_empty_requests(oracle):
     b = W.ragged_small(41, "bf16", prefix_lens=(0, 0, 17, 64), new_lens=(1, 0, 1, 1))
     _check_full(oracle, b, "single rows")
