@@ -468,6 +468,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    import __graft_entry__
+    __graft_entry__.ensure_built()            # compiles only if nothing is built yet
     binding.load()
 
     if args.calibrate_copy:
