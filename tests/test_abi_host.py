@@ -167,3 +167,28 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0
     assert "one GPU" in r.stderr
     assert r.stdout.strip() == ""
+
+
+def test_work_group_shape_follows_the_batch(monkeypatch):
+    """The bf16 attention kernel runs as four waves (32-token units) when the batch's 64-token blocks
+    average fewer than 128 tile steps, else as eight (64-token units); the size query of the gather
+    diagnostic reports the unit the attention call will use, without touching a device."""
+    monkeypatch.delenv("PBKV_ATTN_WAVES", raising=False)
+
+    def units(batch, prefix, new, max_pages):
+        shape = _shape(batch=batch, num_pages=4 * max_pages, max_pages_per_req=max_pages)
+        return binding.gather_probe(shape, FAKE, FAKE, FAKE, FAKE, np.full(batch, prefix, np.int32),
+                                    np.full(batch, new, np.int32), None, stream=0)
+
+    n, tok = units(4, 2048, 512, 160)                 # the benchmark batch: 34-42 steps per block
+    assert tok == 32 and n == 4 * 16 * 8
+    n, tok = units(4, 32768, 2048, 2200)              # long histories: > 500 steps per block
+    assert tok == 64 and n == 4 * 32 * 8
+    n, tok = units(2, 8000, 64, 520)                  # 127 steps: just below the switch
+    assert tok == 32
+    n, tok = units(2, 8064, 64, 520)                  # 128 steps
+    assert tok == 64
+    monkeypatch.setenv("PBKV_ATTN_WAVES", "8")
+    assert units(4, 2048, 512, 160)[1] == 64
+    monkeypatch.setenv("PBKV_ATTN_WAVES", "4")
+    assert units(4, 32768, 2048, 2200)[1] == 32
