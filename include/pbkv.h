@@ -14,12 +14,21 @@
  *     page-locked host memory (hipHostMalloc, or a pinned torch tensor) that
  *     the GPU reads while the stream runs.
  *   - The caller owns every buffer and the stream.  The library keeps no
- *     caller pointer after the call returns.  It owns a small per-device ring
- *     of pinned descriptor memory, created on first use and released at
- *     process exit.
+ *     caller pointer after the call returns.  Per device it owns a ring of
+ *     pinned descriptor memory (8 MiB) and, per stream it has seen (up to 8; a
+ *     ninth replaces the one used longest ago, after draining the device), 2 MiB
+ *     of device memory holding the work lists of recent calls, so that a call
+ *     that repeats the shape and lengths of an earlier call on that stream (the
+ *     next layer of the same batch) builds and uploads nothing.  All of it is
+ *     created on first use and released at process exit.
  *   - `stream` is a hipStream_t passed as void*; NULL is the default stream.
  *     Calls validate on the host, enqueue on `stream`, and return without
  *     waiting.  Buffers must stay valid until the stream has run the work.
+ *     A stream that is being captured into a graph is refused
+ *     (PBKV_ERR_DEVICE): the work lists live in library memory that later
+ *     calls reuse, so a replay would read lists that are gone.
+ *   - Device pointers are checked for their kind (device / pinned) the first
+ *     time the calling thread passes an address; later calls trust it.
  *   - Return value: PBKV_OK or a negative pbkv_status.  On an argument error
  *     nothing is enqueued.  pbkv_last_error() gives a thread-local message.
  *   - Layouts are row-major, innermost dimension last:
@@ -139,9 +148,10 @@ int pbkv_swap_in_pages(const pbkv_shape *shape, const void *host_pages,
  * token is expected to be in the pool already (append first).  context_lens[r] == 0 gives a zero row.
  *   q, out      : device, [batch][H_q][d], bf16 (other dtypes: PBKV_ERR_DTYPE)
  *   kv_pool, block_table : device, read only;   context_lens : host int32 [batch]
- * fp32 accumulation, probabilities kept in fp32, one final rounding to bf16.  The library keeps a
- * device scratch buffer for the partial results of context slices (allocated on first use, grown
- * on demand); calls on different streams of one device must not overlap.
+ * fp32 accumulation, probabilities kept in fp32, one final rounding to bf16.  The library keeps,
+ * per stream, a device scratch buffer for the partial results of context slices (8 MiB on first
+ * use; a call that needs more drains that stream and re-allocates); calls on different streams
+ * use different buffers and may overlap.
  * Errors: NULL pointers, unsupported shape, negative lengths, ceil(len / P) > max_pages_per_req.
  */
 int pbkv_paged_decode(const pbkv_shape *shape, const void *q, const void *kv_pool,
@@ -183,6 +193,15 @@ int pbkv_gather_probe(const pbkv_shape *shape, const void *k_new, const void *v_
                       const void *kv_pool, const int32_t *block_table,
                       const int32_t *prefix_lens, const int32_t *new_lens, uint32_t *unit_xor,
                       int64_t unit_capacity, int64_t *n_units, int32_t *unit_tokens, void *stream);
+
+/*
+ * Work-group shape of the bf16 attention kernel, for tests and tuning: 4 or 8 makes every later
+ * pbkv_prefix_prefill / pbkv_gather_probe launch of this process use work-groups of that many
+ * waves (32 or 64 suffix tokens per unit at a query/KV head ratio of 4), 0 returns to the
+ * library's own choice per launch.  Results do not depend on it bit for bit.  Any other value:
+ * PBKV_ERR_SHAPE.
+ */
+int pbkv_set_attn_waves(int waves);
 
 /* Thread-local, library-owned description of the last error on this thread ("" if none). */
 const char *pbkv_last_error(void);

@@ -11,7 +11,7 @@ import os
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("PBKV_LIB", os.path.join(HERE, "libpbkv.so"))
+LIB_PATH = os.path.join(HERE, "libpbkv.so")
 
 PBKV_BF16, PBKV_F32 = 0, 1
 STATUS = {0: "PBKV_OK", -1: "PBKV_ERR_NULL", -2: "PBKV_ERR_SHAPE", -3: "PBKV_ERR_DTYPE",
@@ -57,6 +57,8 @@ def load():
         lib.pbkv_gather_probe.restype = ctypes.c_int
         lib.pbkv_gather_probe.argtypes = [sp, vp, vp, vp, i32p, i32p, i32p, vp, ctypes.c_int64,
                                           ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32), vp]
+        lib.pbkv_set_attn_waves.restype = ctypes.c_int
+        lib.pbkv_set_attn_waves.argtypes = [ctypes.c_int]
         lib.pbkv_page_bytes.restype = ctypes.c_int64
         lib.pbkv_page_bytes.argtypes = [sp]
         lib.pbkv_last_error.restype = ctypes.c_char_p
@@ -107,6 +109,11 @@ def page_bytes(shape):
 
 def version():
     return load().pbkv_version().decode()
+
+
+def set_attn_waves(waves):
+    """4 or 8: work-group shape of every later bf16 attention launch; 0: the library chooses."""
+    _check(load().pbkv_set_attn_waves(int(waves)))
 
 
 def prefix_prefill(shape, q, k_new, v_new, kv_pool, block_table, prefix_lens, new_lens, out,

@@ -9,11 +9,11 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-OBJ = os.environ.get("PBKV_OBJ_DIR", os.path.join(HERE, "_build"))
-LIB = os.environ.get("PBKV_LIB_OUT", os.path.join(HERE, "libpbkv.so"))
+OBJ = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "libpbkv.so")
 SOURCES = ["pbkv_api.hip", "attn_bf16.hip", "attn_f32.hip", "scatter.hip", "decode_bf16.hip", "predictor.hip", "policy.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"] + os.environ.get("PBKV_EXTRA_FLAGS", "").split()
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
 def _compile(src: str) -> str:

@@ -49,8 +49,8 @@
 // only when a row maximum exceeds it by more than 2^8.
 #include "pbkv_internal.h"
 
-#include <cstdio>
-#include <cstdlib>
+#include <algorithm>
+#include <atomic>
 #include <utility>
 
 namespace pbkv {
@@ -64,10 +64,7 @@ typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 typedef __attribute__((address_space(3))) void lds_void;
 
 constexpr int BN = 64;   // keys per LDS tile (two 32-key blocks)
-#ifndef PBKV_PF
-#define PBKV_PF 3
-#endif
-constexpr int PF = PBKV_PF;    // LDS operand prefetch distance, in MFMA steps
+constexpr int PF = 3;    // LDS operand prefetch distance, in MFMA steps
 [[maybe_unused]] constexpr float RESCALE_SUM = 4096.0f;  // a lane's probability sum over one block above this moves the reference
 
 template <int D, int NW>
@@ -109,10 +106,13 @@ static __device__ __forceinline__ void static_for(F &&f, std::integer_sequence<i
 // (three dependent fetches before the first tile step, the output stores after the last) with the
 // other's arithmetic and cut the work twice as fine, which wins when work-groups are short or few:
 // measured +3 % / +5 % / 0 / -5 % on launches whose 64-token blocks average 37 / 70 / 152 / 513
-// tile steps.  PBKV_ATTN_WAVES=4|8 overrides the choice.
+// tile steps.  attn_bf16_force_waves(4|8) overrides the choice for the whole process (0: automatic).
+static std::atomic<int> g_forced_waves{0};
+void attn_bf16_force_waves(int waves) { g_forced_waves.store(waves == 4 || waves == 8 ? waves : 0); }
+int attn_bf16_forced_waves() { return g_forced_waves.load(); }
+
 int attn_bf16_waves(const int32_t *prefix_lens, const int32_t *new_lens, int batch) {
-    const char *e = getenv("PBKV_ATTN_WAVES");            // read on every call: tests switch it
-    const int forced = e ? atoi(e) : 0;
+    const int forced = g_forced_waves.load();
     if (forced == 4 || forced == 8) return forced;
     int64_t steps = 0, blocks = 0;
     for (int r = 0; r < batch; r++) {
@@ -147,17 +147,7 @@ int attn_bf16_tile_tokens(int /*head_dim*/, int group, int waves) {
 // Two waves share a SIMD's issue port, and the arbiter serves the older wave first: its softmax
 // arithmetic would keep the younger wave's MFMAs off the matrix pipe.  Every MFMA is therefore
 // issued at raised wave priority, so that a waiting MFMA of either wave goes before VALU work.
-#ifndef PBKV_NO_MFMA_PRIO
 #define MFMA_PRIO(x) __builtin_amdgcn_s_setprio(x)
-#else
-#define MFMA_PRIO(x) do {} while (0)
-#endif
-
-#ifdef PBKV_TRACE
-#define TRACE_MARK(k) do { unsigned long long now_ = __builtin_amdgcn_s_memtime(); tr_acc[k] += now_ - tr_last; tr_last = now_; } while (0)
-#else
-#define TRACE_MARK(k) do {} while (0)
-#endif
 
 // PROBE = true builds the gather diagnostic: the same work units, block-table walk, buffer
 // descriptors, loads into LDS and barriers, but instead of the arithmetic every wave XORs the
@@ -170,9 +160,6 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
     constexpr int H = Gm::H;
     constexpr int NT = 64 * NW;
     constexpr int ROWB = Gm::ROWB;
-#ifdef PBKV_TRACE
-    const unsigned long long tr_entry = __builtin_amdgcn_s_memrealtime();
-#endif
 
     // four separate arrays: the direct-to-LDS loads of one buffer provably do not alias
     // the operand reads of the others
@@ -188,6 +175,9 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
     const int nsplit = G / Gw;
     const int split = rest % nsplit;
     const TileDesc td = p.tiles[rest / nsplit];
+    // a launch that read its work list from the host's descriptor ring leaves a copy in device
+    // memory for later launches over the same batch
+    if (p.mirror != nullptr && kvh == 0 && split == 0 && tid == 0) p.mirror[rest / nsplit] = td;
     const int head = kvh * G + split * Gw + (w % Gw);
     const int tile_tok = 32 * (NW / Gw);
     const int tok_base = td.tok0 + (w / Gw) * 32;
@@ -199,13 +189,6 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
     const int TPF = td.prefix_len / BN;                    // full prefix tiles
     const int n_tiles = TP + (tok_end + BN - 1) / BN;
     const int wave_min_tok = min(tok_base, td.new_len - 1);   // smallest token index in this wave
-
-    // zero the V buffers once: rows past the last key are never loaded, and 0 * stale bits
-    // must not be able to produce a NaN in the PV product
-    for (int i = tid; i < Gm::TILEB / 16; i += NT) {
-        *(uint4 *)(sV0 + i * 16) = make_uint4(0, 0, 0, 0);
-        *(uint4 *)(sV1 + i * 16) = make_uint4(0, 0, 0, 0);
-    }
 
     // ---- Q^T operands, pre-scaled: lane (li, lh) holds c * Q[token li][16*dc + 8*lh .. +7] ----
     // c = log2(e)/sqrt(D), so the MFMA result is the score in log2 units (Eq. softmax(QK^T/sqrt(d)))
@@ -266,7 +249,7 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
             asm volatile("; source: prefix page");
         } else {
             const int s0 = (t - TP) * BN + w * Gm::RW;         // first suffix token of this wave's rows
-            const int srows = tok_end - s0;                    // >= RW: all of them (no lane reaches further)
+            const int srows = min(tok_end - s0, Gm::RW);       // the wave's own rows (no lane reaches further)
             const int64_t off = (td.row0 + s0) * (int64_t)row_pitch;
             s.k = kn_h + off;
             s.v = vn_h + off;
@@ -366,16 +349,16 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
     };
 
     // ---- prologue: K(0) into LDS ---------------------------------------------------------------
-    __syncthreads();                                      // V buffers zeroed
     Src prev = tile_src(0);
     issue_loads(prev.k, prev.nrec, sK0, offs_k(0));
+    // while that fetch is in flight, zero the V buffers once: rows past the last key are never
+    // loaded, and 0 * stale bits must not be able to produce a NaN in the PV product
+    for (int i = tid; i < Gm::TILEB / 16; i += NT) {
+        *(uint4 *)(sV0 + i * 16) = make_uint4(0, 0, 0, 0);
+        *(uint4 *)(sV1 + i * 16) = make_uint4(0, 0, 0, 0);
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0): the loads have landed in LDS
-    __syncthreads();
-#ifdef PBKV_TRACE
-    unsigned long long tr_acc[6] = {0, 0, 0, 0, 0, 0};
-    unsigned long long tr_last = __builtin_amdgcn_s_memtime();
-    const unsigned long long tr_t0 = tr_last, tr_r0 = __builtin_amdgcn_s_memrealtime();
-#endif
+    __syncthreads();                                      // ... and the V buffers are zero
 
     if constexpr (PROBE) {
         // valid rows of tile t (0 outside the tile range)
@@ -432,9 +415,47 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
     ones[0] = (__bf16)1.0f;
     ones[1] = (__bf16)1.0f;
 
+    // The common path never computes a row maximum.  The probabilities of the previous block were
+    // formed under the current reference M; their lane sum lb tells whether that was safe: a sum
+    // above 2^12 (or inf) means some score ran far ahead of M.  Then -- rarely -- the block is redone:
+    // its scores are still in Tn (the score product of the iteration has not overwritten them yet), M
+    // moves up to their row maximum, O and the row sum (which hold exactly the blocks before it) are
+    // rescaled, and its probabilities are formed again.  The first block is always redone, which sets
+    // M to its row maximum whatever the magnitude of the scores (key 0 is visible to every row, so
+    // that maximum is finite).
+    auto redo_block = [&](f32x16 &Tc, f32x16 &Tn, bf16x8 (&Pp)[2], bool first_check) __attribute__((always_inline)) {
+        float mxp = Tn[0];
+#pragma unroll
+        for (int r = 1; r < 16; r++) mxp = fmaxf(mxp, Tn[r]);
+        mxp = xmax32(mxp);
+        const float d = first_check ? mxp : fmaxf(mxp, 0.f);      // later moves never lower the reference
+        const float alpha = first_check ? 1.f : __builtin_amdgcn_exp2f(-d);
+        l_part *= alpha;
+        // whole-vector updates: the 16-register accumulator tuples stay where they are
+#pragma unroll
+        for (int db = 0; db < Gm::DB; db++) O[db] *= alpha;
+        Tn -= d;
+        Tc -= d;
+        negM -= d;
+        lb = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+            f32x2 pv;
+            pv[0] = __builtin_amdgcn_exp2f(Tn[r]);
+            pv[1] = __builtin_amdgcn_exp2f(Tn[r + 1]);
+            const bf16x2 pk = __builtin_convertvector(pv, bf16x2);
+            Pp[r / 8][r % 8] = pk[0];
+            Pp[r / 8][r % 8 + 1] = pk[1];
+            lb = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lb, false);
+        }
+        // (a block that still overflows after its own maximum became the reference cannot exist)
+    };
+
     // ---- tile step j = iterations 2j-1 and 2j: K(j) and V(j-1) are read, K(j+1) and V(j) are fetched.
-    // Step 0 starts from empty state (t = -inf, P = 0, V(-1) = the zeroed buffer) and sets the reference
-    // at its second iteration; step n_tiles only drains the pipeline (its scores are fully masked).
+    // The pipeline is filled by a step of its own (scores of tile 0 only: there is nothing to
+    // exponentiate or multiply yet) and drained by another (probabilities of the last block and the
+    // products of the last tile only: there are no further scores); the n_tiles - 1 steps between
+    // them are the full step below.
     //
     // The 4H MFMAs of a step take their LDS operands (K rows for the score halves, transposed V
     // for the product halves) from ONE stream that runs PF MFMAs ahead, across the half and
@@ -444,7 +465,6 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
         constexpr int NM = 4 * H;                          // MFMAs per step
         constexpr int LD_SP = H / (2 * Gm::NI);            // MFMAs between two tile loads
         static_assert(LD_SP >= 1, "the tile loads of a step fit its first half iteration");
-        TRACE_MARK(5);
         // sources: K(j+1) now, V(j) from what the previous step found for tile j
         const Src next = tile_src(j + 1);
         const Offs ok = offs_k(j + 1), ov = offs_v(j);
@@ -460,64 +480,18 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
         auto operand = [&](auto mc) {
             constexpr int m = decltype(mc)::value;
             constexpr int i = m / (2 * H), half = (m / H) & 1, s2 = m % H;
-#ifdef ABL_NOLDS
-            return qreg[(s2 + half) % Gm::DC];
-#else
             if constexpr (half == 0) return k_operand(kcur, i, s2);
             else return v_operand(vprev, i, s2);
-#endif
         };
         static_for([&](auto mc) { op[mc.value % (PF + 1)] = operand(mc); }, std::make_integer_sequence<int, PF>{});
 
         auto iteration = [&](auto ic, f32x16 &Tc, f32x16 &Tn, bf16x8 (&Pc)[2], bf16x8 (&Pp)[2], bool first_check) __attribute__((always_inline)) {
             constexpr int i = decltype(ic)::value;
             constexpr int m0 = i * 2 * H;
-            // The common path never computes a row maximum.  The probabilities of the previous block
-            // were formed under the current reference M; their lane sum lb tells whether that was
-            // safe: a sum above 2^12 (or inf) means some score ran far ahead of M.  Then -- rarely --
-            // the block is redone: its scores are still in Tn (the score product of this iteration
-            // has not overwritten them yet), M moves up to their row maximum, O and the row sum
-            // (which hold exactly the blocks before it) are rescaled, and its probabilities are formed
-            // again.  The first block is always redone, which sets M to its row maximum whatever the
-            // magnitude of the scores (key 0 is visible to every row, so that maximum is finite).
-#if !defined(ABL_NOBRANCH) && !defined(ABL_NORESCALE)
-            if (__builtin_expect(first_check || redo, 0)) {
-                float mxp = Tn[0];
-#pragma unroll
-                for (int r = 1; r < 16; r++) mxp = fmaxf(mxp, Tn[r]);
-                mxp = xmax32(mxp);
-                const float d = first_check ? mxp : fmaxf(mxp, 0.f);      // later moves never lower the reference
-                const float alpha = first_check ? 1.f : __builtin_amdgcn_exp2f(-d);
-                l_part *= alpha;
-                // whole-vector updates: the 16-register accumulator tuples stay where they are
-#pragma unroll
-                for (int db = 0; db < Gm::DB; db++) O[db] *= alpha;
-                Tn -= d;
-                Tc -= d;
-                negM -= d;
-                lb = 0.f;
-#pragma unroll
-                for (int r = 0; r < 16; r += 2) {
-                    f32x2 pv;
-                    pv[0] = __builtin_amdgcn_exp2f(Tn[r]);
-                    pv[1] = __builtin_amdgcn_exp2f(Tn[r + 1]);
-                    const bf16x2 pk = __builtin_convertvector(pv, bf16x2);
-                    Pp[r / 8][r % 8] = pk[0];
-                    Pp[r / 8][r % 8 + 1] = pk[1];
-                    lb = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lb, false);
-                }
-                // (a block that still overflows after its own maximum became the reference cannot exist)
-            }
-#endif
-#ifdef ABL_NOBRANCH
-            asm volatile("" : "+v"(negM));                // the reference may have moved: no hoisting of the score product
-#endif
+            if (__builtin_expect(first_check || redo, 0)) redo_block(Tc, Tn, Pp, first_check);
             l_part += lb;
             lb = 0.f;
             auto exp_pair = [&](int r) {                  // scores r, r+1 of the pending block
-#ifdef ABL_NOVALU
-                return;
-#endif
                 f32x2 pv;
                 pv[0] = __builtin_amdgcn_exp2f(Tc[r]);
                 pv[1] = __builtin_amdgcn_exp2f(Tc[r + 1]);
@@ -526,8 +500,6 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
                 Pc[r / 8][r % 8 + 1] = pk[1];
                 lb = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lb, false);   // sum of what PV will use
             };
-            __builtin_amdgcn_sched_barrier(0);
-            TRACE_MARK(0);
             __builtin_amdgcn_sched_barrier(0);
 
             // ---- first half: t(b+1) = K Q^T - M  ||  probabilities of keys 0-15 of block b; tile loads ----
@@ -538,7 +510,6 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
                 MFMA_PRIO(1);
                 Tn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[m % (PF + 1)], qreg[s2], s2 == 0 ? negM : Tn, 0, 0, 0);
                 MFMA_PRIO(0);
-#ifndef ABL_NOLOAD
                 // all tile loads of the step go out in its first half iteration, K and V rows
                 // alternating, one every LD_SP MFMAs: they have the rest of the step to land
                 if constexpr (i == 0 && s2 % LD_SP == 0) {
@@ -546,7 +517,6 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
                     if constexpr (q % 2 == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_k, dst_k, 16, ok.v[li2], 0, li2 * 1024, 0);
                     else __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_v, dst_v, 16, ov.v[li2], 0, li2 * 1024, 0);
                 }
-#endif
                 // four score pairs over H steps
                 if constexpr (H == 8) { if constexpr (s2 % 2 == 0) exp_pair(s2); }
                 else exp_pair(2 * s2);
@@ -555,9 +525,7 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
                 constexpr int s2 = decltype(sc)::value, m = m0 + s2;
                 if constexpr (m == 0) __builtin_amdgcn_sched_group_barrier(SG_DSRD, PF, 0);
                 __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
-#ifndef ABL_NOLOAD
                 if constexpr (i == 0 && s2 % LD_SP == 0) __builtin_amdgcn_sched_group_barrier(SG_VMRD, 1, 0);
-#endif
                 __builtin_amdgcn_sched_group_barrier(SG_VALU, 16 / H, 0);
                 if constexpr (m + PF < NM) __builtin_amdgcn_sched_group_barrier(SG_DSRD, ((m + PF) / H) & 1 ? 2 : 1, 0);
             }, std::make_integer_sequence<int, H>{});
@@ -566,14 +534,9 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
             PIN_V(Pc[0]);
             PIN_V(lb);
             __builtin_amdgcn_sched_barrier(0);
-            TRACE_MARK(1);
-#if !defined(ABL_NOBRANCH) && !defined(ABL_NOMASK)
             if (__builtin_expect(masked, 0)) {
                 if (needs_mask(j, i)) mask_block(Tn, j, i);
             }
-#endif
-            __builtin_amdgcn_sched_barrier(0);
-            TRACE_MARK(2);
             __builtin_amdgcn_sched_barrier(0);
 
             // ---- second half: O += V^T P of block b-1  ||  probabilities of keys 16-31 of block b ----
@@ -598,37 +561,70 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
             PIN_V(Pc[1]);
             PIN_V(lb);
             __builtin_amdgcn_sched_barrier(0);
-            TRACE_MARK(3);
         };
         iteration(IntC<0>{}, T1, T0, P1, P0, j == 1);      // block 0 is redone before its PV product
         iteration(IntC<1>{}, T0, T1, P0, P1, false);
-#ifndef ABL_NOBAR
         __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0): K(j+1), V(j) are in LDS
         __syncthreads();                                  // ... and every wave is done with K(j), V(j-1)
-#endif
-        TRACE_MARK(4);
     };
-    // steps run in pairs so that the LDS buffers are compile-time constants
-    for (int j = 0; j <= n_tiles; j += 2) {
-        step(j, sK0, sK1, sV1, sV0);
-        if (j + 1 <= n_tiles) step(j + 1, sK1, sK0, sV0, sV1);
+    // fill: scores of the two blocks of tile 0 (from the reference 0; the first full or drain step
+    // moves the reference to block 0's row maximum before anything is exponentiated); K(1), V(0) fetched
+    {
+        const Src next = tile_src(1);
+        issue_loads(next.k, next.nrec, sK1, offs_k(1));
+        issue_loads(prev.v, prev.nrec, sV0, offs_v(0));
+        prev = next;
+        static_for([&](auto dc) {
+            T0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_operand(sK0, 0, dc.value), qreg[dc.value], dc.value == 0 ? negM : T0, 0, 0, 0);
+        }, std::make_integer_sequence<int, Gm::DC>{});
+        static_for([&](auto dc) {
+            T1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_operand(sK0, 1, dc.value), qreg[dc.value], dc.value == 0 ? negM : T1, 0, 0, 0);
+        }, std::make_integer_sequence<int, Gm::DC>{});
+        if (0 >= TPF) {
+            if (needs_mask(0, 0)) mask_block(T0, 0, 0);
+            if (needs_mask(0, 1)) mask_block(T1, 0, 1);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
     }
-    l_part += lb;                                          // the drained blocks are fully masked: lb is 0
+    // full steps 1 .. n_tiles - 1, in pairs so that the LDS buffers are compile-time constants
+    for (int j = 1; j < n_tiles; j += 2) {
+        step(j, sK1, sK0, sV0, sV1);
+        if (j + 1 < n_tiles) step(j + 1, sK0, sK1, sV1, sV0);
+    }
+    // drain: probabilities of the last block, products of tile n_tiles - 1 (its V rows were fetched
+    // by the step before and are in the buffer that step wrote)
+    {
+        const char *vlast = (n_tiles - 1) & 1 ? sV1 : sV0;
+        auto exp_all = [&](f32x16 &Tc, bf16x8 (&Pc)[2]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+                f32x2 pv;
+                pv[0] = __builtin_amdgcn_exp2f(Tc[r]);
+                pv[1] = __builtin_amdgcn_exp2f(Tc[r + 1]);
+                const bf16x2 pk = __builtin_convertvector(pv, bf16x2);
+                Pc[r / 8][r % 8] = pk[0];
+                Pc[r / 8][r % 8 + 1] = pk[1];
+                lb = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lb, false);
+            }
+        };
+        auto product = [&](int kb, bf16x8 (&Pp)[2]) __attribute__((always_inline)) {
+            static_for([&](auto sc) {
+                constexpr int s2 = decltype(sc)::value;
+                O[s2 % Gm::DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(vlast, kb, s2), Pp[s2 / Gm::DB], O[s2 % Gm::DB], 0, 0, 0);
+            }, std::make_integer_sequence<int, H>{});
+        };
+        if (n_tiles == 1 || redo) redo_block(T1, T0, P0, n_tiles == 1);
+        l_part += lb;
+        lb = 0.f;
+        exp_all(T1, P1);
+        product(0, P0);
+        if (__any(!(lb <= RESCALE_SUM))) redo_block(T0, T1, P1, false);
+        l_part += lb;
+        lb = 0.f;
+        product(1, P1);
+    }
 
-#ifdef PBKV_TRACE
-    if (p.trace && l == 0 && w == 0 && blockIdx.x < 4096) {
-        unsigned long long *sp = (unsigned long long *)p.trace + 64 * 8 * 8 + blockIdx.x * 4;
-        sp[0] = tr_entry;
-        sp[1] = tr_r0;
-        sp[2] = __builtin_amdgcn_s_memrealtime();
-    }
-    if (p.trace && l == 0 && blockIdx.x < 64) {
-        unsigned long long *tp = (unsigned long long *)p.trace + (blockIdx.x * NW + w) * 8;
-        for (int k = 0; k < 6; k++) tp[k] = tr_acc[k];
-        tp[6] = n_tiles + 1;
-        tp[7] = ((__builtin_amdgcn_s_memtime() - tr_t0) << 24) | ((__builtin_amdgcn_s_memrealtime() - tr_r0) & 0xffffff);
-    }
-#endif
     // ---- epilogue: normalise, round once to bf16, store -----------------------------------
     // register r of O[db] is MFMA row 8*(r/4) + 4*lh + r%4; rows 0-15 are d = 16*db + row,
     // rows 16-31 are d = D/2 + 16*db + (row - 16)
@@ -645,10 +641,6 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
                 *(bf16x4 *)(op + 16 * db + 8 * (b4 & 1) + (D / 2) * (b4 >> 1)) = v;
             }
     }
-#ifdef PBKV_TRACE
-    if (p.trace && l == 0 && w == 0 && blockIdx.x < 2048)
-        ((unsigned long long *)p.trace)[64 * 8 * 8 + blockIdx.x * 4 + 3] = __builtin_amdgcn_s_memrealtime();
-#endif
     }   // !PROBE
 #endif
 }
@@ -660,41 +652,9 @@ static hipError_t launch_one(const AttnParams &p, int G, int Gw, hipStream_t s) 
     return hipGetLastError();
 }
 
-#ifdef PBKV_TRACE
-static void trace_dump(void *dev, int nw) {
-    static int calls = 0;
-    if (++calls != 3) return;
-    hipDeviceSynchronize();
-    static unsigned long long h[64 * 8 * 8 + 8192];
-    hipMemcpy(h, dev, sizeof h, hipMemcpyDeviceToHost);
-    {
-        unsigned long long *sp = h + 64 * 8 * 8, t0 = ~0ull, t1 = 0; int nb = 0;
-        for (int b = 0; b < 2048; b++) if (sp[4 * b]) { nb++; if (sp[4 * b] < t0) t0 = sp[4 * b]; if (sp[4 * b + 3] > t1) t1 = sp[4 * b + 3]; }
-        double pro = 0, loop = 0, epi = 0, first = 0;
-        for (int b = 0; b < 2048; b++) if (sp[4 * b]) { first += sp[4 * b] - t0; pro += sp[4 * b + 1] - sp[4 * b]; loop += sp[4 * b + 2] - sp[4 * b + 1]; epi += sp[4 * b + 3] - sp[4 * b + 2]; }
-        printf("trace: %d blocks, span %.2f us; mean entry delay %.2f us, prologue %.2f us, loop %.2f us, epilogue %.2f us\n", nb, (t1 - t0) / 100.0, first / nb / 100.0, pro / nb / 100.0, loop / nb / 100.0, epi / nb / 100.0);
-        for (int b = 0; b < nb; b += nb / 16) printf("  block %d entry %.2f loop %.2f..%.2f exit %.2f\n", b, (sp[4 * b] - t0) / 100.0, (sp[4 * b + 1] - t0) / 100.0, (sp[4 * b + 2] - t0) / 100.0, (sp[4 * b + 3] - t0) / 100.0);
-    }
-    const char *names[6] = {"top", "half1", "mask", "half2", "barrier", "carry"};
-    for (int b = 0; b < 64; b += 21)
-        for (int w = 0; w < nw; w += 3) {
-            unsigned long long *t = h + (b * nw + w) * 8;
-            printf("trace block %d wave %d tiles %llu:", b, w, t[6]);
-            for (int k = 0; k < 6; k++) printf(" %s=%.0f", names[k], t[6] ? (double)t[k] / t[6] : 0.0);
-            printf(" | life %llu ticks, %.1f us real, clock %.2f GHz", t[7] >> 24, (t[7] & 0xffffff) / 100.0, (t[7] >> 24) / ((t[7] & 0xffffff) * 10.0));
-            printf("\n");
-        }
-}
-#endif
 
 hipError_t launch_attn_bf16(const AttnParams &p0, int head_dim, hipStream_t s) {
     AttnParams p = p0;
-#ifdef PBKV_TRACE
-    static void *trace_buf = nullptr;
-    if (!trace_buf) { hipMalloc(&trace_buf, (64 * 8 * 8 + 8192) * 8); hipMemset(trace_buf, 0, (64 * 8 * 8 + 8192) * 8); }
-    p.trace = trace_buf;
-    struct Dump { void *b; int nw; ~Dump() { trace_dump(b, nw); } } dump{trace_buf, p.waves};
-#endif
     if (p.n_tiles == 0) return hipSuccess;
     const int G = p.Hq / p.Hkv;
     const int Gw = G < 4 ? G : 4;

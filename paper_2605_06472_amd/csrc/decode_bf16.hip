@@ -29,6 +29,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 constexpr int DEC_WAVES = 4;
+[[maybe_unused]] constexpr int DEC_NBUF = 2;            // page buffers per wave (three were measured: not faster)
 [[maybe_unused]] constexpr float DEC_RESCALE_LOG2 = 8.0f;
 
 int decode_heads_per_group(int group) { return group < 8 ? group : 8; }
@@ -57,6 +58,7 @@ void decode_bf16_kernel(DecodeParams p, int G) {
     bid /= nsplit_g;
     const int kvh = bid % p.Hkv;
     const DecodeUnit un = p.units[bid / p.Hkv];
+    if (p.mirror_units != nullptr && kvh == 0 && hs == 0 && threadIdx.x == 0) p.mirror_units[bid / p.Hkv] = un;
     const int g = l >> 4, c = l & 15;
     const int head0 = kvh * G + hs * GW;
 
@@ -180,10 +182,7 @@ void decode_bf16_kernel(DecodeParams p, int G) {
         }
     };
 
-#ifndef DEC_NBUF
-#define DEC_NBUF 2
-#endif
-    // the pages NBUF-1 ahead are in flight while one is being worked on
+    // the pages DEC_NBUF-1 ahead are in flight while one is being worked on
     PageRegs rg[DEC_NBUF];
 #pragma unroll
     for (int b = 0; b < DEC_NBUF - 1; b++)
@@ -273,6 +272,7 @@ __global__ __launch_bounds__(D * GW) void decode_merge_kernel(DecodeParams p, in
     const int kvh = bid % p.Hkv;
     const int req = bid / p.Hkv;
     const DecodeReq rq = p.reqs[req];
+    if (p.mirror_reqs != nullptr && kvh == 0 && hs == 0 && threadIdx.x == 0) p.mirror_reqs[req] = rq;
     const int d = threadIdx.x % D, h = threadIdx.x / D;
     constexpr int PS = (GW * (D + 2) + 3) & ~3;
     const int64_t stride = (int64_t)p.Hkv * nsplit_g * PS;             // between consecutive slices

@@ -89,8 +89,27 @@ int check_aligned(const void *p, const char *name) {
     return PBKV_OK;
 }
 
+// Pointer kinds are asked of the runtime the first time the calling thread sees an address and
+// remembered after that (a model passes the same buffers layer after layer, and the query costs
+// about as much as a kernel launch).  The check catches a host pointer passed by mistake; it is no
+// guard against a buffer that is freed and re-allocated as something else between calls.
+enum PtrKind : uint8_t { KIND_NONE = 0, KIND_DEVICE = 1, KIND_PINNED = 2 };
+struct PtrMemo {
+    const void *ptr[32] = {};
+    uint8_t kind[32] = {};
+    int next = 0;
+    bool has(const void *p, uint8_t k) const {
+        for (int i = 0; i < 32; i++)
+            if (ptr[i] == p && kind[i] == k) return true;
+        return false;
+    }
+    void put(const void *p, uint8_t k) { ptr[next] = p; kind[next] = k; next = (next + 1) & 31; }
+};
+thread_local PtrMemo g_ptr_memo;
+
 // The pointer must be something a kernel on the current device may dereference.
 int check_device_ptr(const void *p, const char *name) {
+    if (g_ptr_memo.has(p, KIND_DEVICE)) return PBKV_OK;
     hipPointerAttribute_t a;
     hipError_t e = hipPointerGetAttributes(&a, p);
     if (e != hipSuccess) {
@@ -99,59 +118,93 @@ int check_device_ptr(const void *p, const char *name) {
     }
     if (a.type != hipMemoryTypeDevice && a.type != hipMemoryTypeManaged)
         return fail(PBKV_ERR_DEVICE, "%s: expected device memory", name);
+    g_ptr_memo.put(p, KIND_DEVICE);
     return PBKV_OK;
 }
 
 int check_pinned_ptr(const void *p, const char *name, const void **dev_view) {
+    *dev_view = p;               // pinned memory shares one virtual address between host and device
+    if (g_ptr_memo.has(p, KIND_PINNED)) return PBKV_OK;
     hipPointerAttribute_t a;
     hipError_t e = hipPointerGetAttributes(&a, p);
     if (e != hipSuccess) {
         (void)hipGetLastError();
         return fail(PBKV_ERR_DEVICE, "%s: not pinned host memory (%s)", name, hipGetErrorString(e));
     }
-    if (a.type != hipMemoryTypeHost && a.type != hipMemoryTypeManaged && a.type != hipMemoryTypeDevice)
+    if (a.type != hipMemoryTypeHost && a.type != hipMemoryTypeManaged)
         return fail(PBKV_ERR_DEVICE, "%s: expected pinned host memory", name);
-    // pinned memory shares one virtual address between host and device
-    *dev_view = p;
+    g_ptr_memo.put(p, KIND_PINNED);
     return PBKV_OK;
 }
 
-// ---- per-device ring of pinned, device-mapped descriptor memory ---------------------------
-// Work lists are written here by the host and read by the kernels through the mapped
-// pointer; a region is reused only after the event recorded behind its kernel has fired.
+// ---- per-device state -----------------------------------------------------------------------
+// (1) A ring of pinned, device-mapped descriptor memory.  Work lists are written here by the host
+//     and read by the kernels through the mapped pointer (no copy in front of a kernel); a region
+//     is reused only after the event recorded behind its kernel has fired.
+// (2) Per stream, a small cache of work lists in device memory.  A launch that reads its list from
+//     the ring also stores a copy there (every work-group writes back the descriptor it read), and
+//     a later call on the same stream with the same shape and lengths -- the next layer of the same
+//     batch -- launches straight from that copy: no list is built, nothing is copied, no event is
+//     recorded, and no work-group reads over the host link.  Slots are only ever written and read
+//     by kernels of one stream, so stream order is all the protection they need.
+// (3) Per stream, the scratch buffer of the decode kernels (partials of the context slices), for
+//     the same reason: calls on different streams never share one.
 struct Ring {
     char *host = nullptr;
     char *dev = nullptr;
-    char *mirror = nullptr;          // device-memory copy of the ring (descriptor placement "device")
     size_t cap = 0, head = 0;
     struct Pending { hipEvent_t ev; size_t begin, end; };
     std::deque<Pending> pending;
     std::vector<hipEvent_t> spare;
-    std::mutex mu;
 };
 constexpr size_t RING_BYTES = 8u << 20;
 constexpr int MAX_DEVICES = 16;
-Ring g_rings[MAX_DEVICES];
+constexpr int PLAN_SLOTS = 16;                  // cached work lists per stream
+constexpr size_t PLAN_SLOT_BYTES = 128u << 10;  // longer lists are not cached
+constexpr int MAX_STREAM_CACHES = 8;            // streams with a cache, per device
 
-struct Lease { Ring *ring; size_t begin, end; char *host; char *dev; };
+enum PlanKind { PLAN_ATTN = 1, PLAN_APPEND = 2, PLAN_DECODE = 3 };
+struct Plan {
+    bool valid = false;
+    int kind = 0, forced_waves = 0;
+    pbkv_shape shape{};
+    std::vector<int32_t> lens;   // the host arrays the list was cut from, back to back
+    int32_t n_a = 0, n_b = 0;    // items (tiles | runs | slices, requests)
+    int32_t waves = 0;
+    int64_t aux = 0;             // decode: bytes of scratch the launch needs
+    uint64_t stamp = 0;
+};
+struct StreamCache {
+    bool used = false;
+    hipStream_t stream = nullptr;
+    uint64_t stamp = 0;
+    char *arena = nullptr;       // PLAN_SLOTS * PLAN_SLOT_BYTES of device memory
+    Plan plans[PLAN_SLOTS];
+    float *scratch = nullptr;    // decode partials
+    size_t scratch_cap = 0;
+};
+struct DevState {
+    std::mutex mu;               // held from the first look at this state until the kernels are enqueued
+    Ring ring;
+    StreamCache sc[MAX_STREAM_CACHES];
+    uint64_t clock = 0;
+};
+DevState g_dev[MAX_DEVICES];
 
-// Where kernels read their work lists from.  Default: the pinned ring itself, through its
-// device-mapped address (no copy in front of a kernel).  PBKV_DESCRIPTORS=device: a
-// device-memory mirror, filled by a small stream-ordered copy per call -- for callers that run
-// kernels beside bulk host-link traffic, where a work-group's descriptor read over the link
-// would queue behind that traffic.
-bool descriptors_in_device_memory() {
-    static const bool v = [] { const char *e = getenv("PBKV_DESCRIPTORS"); return e && std::string(e) == "device"; }();
-    return v;
-}
-
-int ring_acquire(size_t bytes, Lease *out) {
+int device_state(DevState **out) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
     if (dev < 0 || dev >= MAX_DEVICES) return fail(PBKV_ERR_DEVICE, "device index %d unsupported", dev);
-    Ring &r = g_rings[dev];
-    std::lock_guard<std::mutex> lk(r.mu);
+    *out = &g_dev[dev];
+    return PBKV_OK;
+}
+
+struct Lease { Ring *ring; size_t begin, end; char *host; char *dev; };
+
+int ring_acquire(DevState &ds, size_t bytes, Lease *out) {
+    Ring &r = ds.ring;
+    hipError_t e;
     if (!r.host) {
         void *h = nullptr, *d = nullptr;
         e = hipHostMalloc(&h, RING_BYTES, hipHostMallocMapped);
@@ -161,12 +214,6 @@ int ring_acquire(size_t bytes, Lease *out) {
         r.host = (char *)h;
         r.dev = (char *)d;
         r.cap = RING_BYTES;
-        if (descriptors_in_device_memory()) {
-            void *m = nullptr;
-            e = hipMalloc(&m, RING_BYTES);
-            if (e != hipSuccess) return fail_hip(e, "hipMalloc(descriptor ring mirror)");
-            r.mirror = (char *)m;
-        }
     }
     bytes = (bytes + 255) & ~(size_t)255;
     if (bytes > r.cap / 2) return fail(PBKV_ERR_LIMIT, "work list of %zu bytes exceeds the descriptor ring", bytes);
@@ -186,23 +233,13 @@ int ring_acquire(size_t bytes, Lease *out) {
         }
     }
     r.head = en;
-    *out = Lease{&r, b, en, r.host + b, (r.mirror ? r.mirror : r.dev) + b};
+    *out = Lease{&r, b, en, r.host + b, r.dev + b};
     return PBKV_OK;
-}
-
-// Make what the host wrote into the lease visible at lease.dev: nothing to do when the kernels
-// read the pinned ring through its mapped address, one small copy on the stream when they read
-// the device-memory mirror.
-int ring_commit(const Lease &l, size_t bytes, hipStream_t s) {
-    if (!l.ring->mirror || bytes == 0) return PBKV_OK;
-    hipError_t e = hipMemcpyAsync(l.dev, l.host, bytes, hipMemcpyHostToDevice, s);
-    return e == hipSuccess ? PBKV_OK : fail_hip(e, "hipMemcpyAsync(descriptors)");
 }
 
 // Record "the kernels reading this lease are enqueued" on the stream.
 int ring_release(const Lease &l, hipStream_t s) {
     Ring &r = *l.ring;
-    std::lock_guard<std::mutex> lk(r.mu);
     hipEvent_t ev;
     if (!r.spare.empty()) {
         ev = r.spare.back();
@@ -217,30 +254,108 @@ int ring_release(const Lease &l, hipStream_t s) {
     return PBKV_OK;
 }
 
-// Device scratch of the decode kernels (partials of the context slices): one buffer per device,
-// grown on demand and kept until the process ends.  Calls that use it must not overlap on
-// different streams of one device.
-int decode_scratch(size_t bytes, float **out) {
-    static std::mutex mu;
-    static std::vector<std::pair<void *, size_t>> per_device;
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
-    std::lock_guard<std::mutex> lock(mu);
-    if ((int)per_device.size() <= dev) per_device.resize(dev + 1, {nullptr, 0});
-    auto &slot = per_device[dev];
-    if (slot.second < bytes) {
-        if (slot.first) {
-            if ((e = hipDeviceSynchronize()) != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
-            (void)hipFree(slot.first);
-            slot = {nullptr, 0};
+// The cache of the stream; a stream seen for the first time takes an unused entry, or the entry
+// used longest ago (its slots may still be read by that other stream's kernels: the device is
+// drained first -- this only happens to callers that rotate over more than MAX_STREAM_CACHES streams).
+int stream_cache(DevState &ds, hipStream_t st, StreamCache **out) {
+    StreamCache *pick = nullptr;
+    for (auto &c : ds.sc) {
+        if (c.used && c.stream == st) {
+            c.stamp = ++ds.clock;
+            *out = &c;
+            return PBKV_OK;
         }
-        const size_t cap = std::max(bytes + bytes / 2, (size_t)4 << 20);
+        if (!pick || (pick->used && (!c.used || c.stamp < pick->stamp))) pick = &c;
+    }
+    hipError_t e;
+    if (pick->used) {
+        if ((e = hipDeviceSynchronize()) != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
+        for (auto &pl : pick->plans) pl.valid = false;
+    }
+    if (!pick->arena) {
+        void *m = nullptr;
+        if ((e = hipMalloc(&m, PLAN_SLOTS * PLAN_SLOT_BYTES)) != hipSuccess) return fail_hip(e, "hipMalloc(work-list cache)");
+        pick->arena = (char *)m;
+    }
+    pick->used = true;
+    pick->stream = st;
+    pick->stamp = ++ds.clock;
+    *out = pick;
+    return PBKV_OK;
+}
+
+bool same_shape(const pbkv_shape &a, const pbkv_shape &b) {
+    return a.batch == b.batch && a.num_q_heads == b.num_q_heads && a.num_kv_heads == b.num_kv_heads &&
+           a.head_dim == b.head_dim && a.page_size == b.page_size && a.dtype == b.dtype;
+}
+
+// The cached list for (kind, shape, lengths), or null.  `b` may be null (one array only).
+Plan *find_plan(DevState &ds, StreamCache &c, int kind, const pbkv_shape *s, int forced_waves, const int32_t *a,
+                const int32_t *b, char **dev) {
+    const size_t n = (size_t)s->batch;
+    for (int i = 0; i < PLAN_SLOTS; i++) {
+        Plan &pl = c.plans[i];
+        if (!pl.valid || pl.kind != kind || pl.forced_waves != forced_waves || !same_shape(pl.shape, *s)) continue;
+        if (pl.lens.size() != (b ? 2 * n : n)) continue;
+        if (memcmp(pl.lens.data(), a, n * sizeof(int32_t)) != 0) continue;
+        if (b && memcmp(pl.lens.data() + n, b, n * sizeof(int32_t)) != 0) continue;
+        pl.stamp = ++ds.clock;
+        *dev = c.arena + (size_t)i * PLAN_SLOT_BYTES;
+        return &pl;
+    }
+    return nullptr;
+}
+
+// The slot a new list goes to (least recently used); the caller fills in counts and marks it valid.
+Plan *new_plan(DevState &ds, StreamCache &c, int kind, const pbkv_shape *s, int forced_waves, const int32_t *a,
+               const int32_t *b, char **dev) {
+    int pick = 0;
+    for (int i = 0; i < PLAN_SLOTS; i++) {
+        if (!c.plans[i].valid) { pick = i; break; }
+        if (c.plans[i].stamp < c.plans[pick].stamp) pick = i;
+    }
+    Plan &pl = c.plans[pick];
+    const size_t n = (size_t)s->batch;
+    pl.valid = false;
+    pl.kind = kind;
+    pl.forced_waves = forced_waves;
+    pl.shape = *s;
+    pl.lens.assign(a, a + n);
+    if (b) pl.lens.insert(pl.lens.end(), b, b + n);
+    pl.stamp = ++ds.clock;
+    *dev = c.arena + (size_t)pick * PLAN_SLOT_BYTES;
+    return &pl;
+}
+
+// Scratch of the decode kernels for this stream: grown on demand (the stream is drained first, its
+// kernels are the only readers) and kept until the process ends.
+int decode_scratch(StreamCache &c, size_t bytes, float **out) {
+    if (c.scratch_cap < bytes) {
+        hipError_t e;
+        if (c.scratch) {
+            if ((e = hipStreamSynchronize(c.stream)) != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
+            (void)hipFree(c.scratch);
+            c.scratch = nullptr;
+            c.scratch_cap = 0;
+        }
+        const size_t cap = std::max(bytes + bytes / 2, (size_t)8 << 20);
         void *ptr = nullptr;
         if ((e = hipMalloc(&ptr, cap)) != hipSuccess) return fail_hip(e, "hipMalloc (decode scratch)");
-        slot = {ptr, cap};
+        c.scratch = (float *)ptr;
+        c.scratch_cap = cap;
     }
-    *out = (float *)slot.first;
+    *out = c.scratch;
+    return PBKV_OK;
+}
+
+// Work lists live in library-owned memory that later calls reuse, so a captured graph would
+// replay against lists that are gone: the entry points that use them refuse a capturing stream.
+int check_not_capturing(hipStream_t st, const char *who) {
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    hipError_t e = hipStreamIsCapturing(st, &status);
+    if (e != hipSuccess) return fail_hip(e, "hipStreamIsCapturing");
+    if (status != hipStreamCaptureStatusNone)
+        return fail(PBKV_ERR_DEVICE, "%s: the stream is being captured into a graph; this call cannot be replayed", who);
     return PBKV_OK;
 }
 
@@ -253,6 +368,7 @@ constexpr int MI355X_CUS = 256;
 int build_tiles(const pbkv_shape *s, const int32_t *prefix_lens, const int32_t *new_lens, int T,
                 std::vector<pbkv::TileDesc> *out, int wgs_per_tile = 1, int resident_pairs_wgs = 0) {
     std::vector<pbkv::TileDesc> &tiles = *out;
+    tiles.clear();
     int64_t row0 = 0;
     for (int r = 0; r < s->batch; r++) {
         for (int t0 = 0; t0 < new_lens[r]; t0 += T) {
@@ -280,17 +396,31 @@ int build_tiles(const pbkv_shape *s, const int32_t *prefix_lens, const int32_t *
     return PBKV_OK;
 }
 
+thread_local std::vector<pbkv::TileDesc> tl_tiles;
+thread_local std::vector<pbkv::AppendDesc> tl_runs;
+thread_local std::vector<pbkv::DecodeUnit> tl_units;
+thread_local std::vector<pbkv::DecodeReq> tl_reqs;
+thread_local std::vector<uint8_t> tl_seen;
+thread_local std::vector<int32_t> tl_ids;
+
 }  // namespace
 
 extern "C" {
 
 const char *pbkv_last_error(void) { return g_err; }
 
-const char *pbkv_version(void) { return "pbkv 0.1 gfx950"; }
+const char *pbkv_version(void) { return "pbkv 0.2 gfx950"; }
 
 int64_t pbkv_page_bytes(const pbkv_shape *s) {
     if (!s || check_shape(s, false) != PBKV_OK) return 0;
     return (int64_t)2 * s->num_kv_heads * s->page_size * s->head_dim * elt_bytes(s->dtype);
+}
+
+int pbkv_set_attn_waves(int waves) {
+    g_err[0] = 0;
+    if (waves != 0 && waves != 4 && waves != 8) return fail(PBKV_ERR_SHAPE, "pbkv_set_attn_waves: %d (0, 4 or 8)", waves);
+    pbkv::attn_bf16_force_waves(waves);
+    return PBKV_OK;
 }
 
 int pbkv_prefix_prefill(const pbkv_shape *s, const void *q, const void *k_new, const void *v_new,
@@ -313,32 +443,61 @@ int pbkv_prefix_prefill(const pbkv_shape *s, const void *q, const void *k_new, c
         (rc = check_device_ptr(block_table, "block_table")) || (rc = check_device_ptr(out, "out")))
         return rc;
 
-    const int G = s->num_q_heads / s->num_kv_heads;
-    const int waves = s->dtype == PBKV_BF16 ? pbkv::attn_bf16_waves(prefix_lens, new_lens, s->batch) : 0;
-    const int T = s->dtype == PBKV_BF16 ? pbkv::attn_bf16_tile_tokens(s->head_dim, G, waves) : pbkv::attn_f32_tile_tokens();
-    std::vector<pbkv::TileDesc> tiles;
-    const int per_tile = s->dtype == PBKV_BF16 ? pbkv::attn_bf16_units_per_tile(s->num_kv_heads, G) : 1;
-    if ((rc = build_tiles(s, prefix_lens, new_lens, T, &tiles, per_tile, waves == 4 ? 2 * MI355X_CUS : 0))) return rc;
-
-    Lease lease;
-    if ((rc = ring_acquire(tiles.size() * sizeof(pbkv::TileDesc), &lease))) return rc;
-    memcpy(lease.host, tiles.data(), tiles.size() * sizeof(pbkv::TileDesc));
-
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = check_not_capturing(st, "pbkv_prefix_prefill"))) return rc;
     pbkv::AttnParams p;
     p.q = q; p.k_new = k_new; p.v_new = v_new; p.kv_pool = kv_pool; p.out = out;
     p.block_table = block_table;
-    p.tiles = (const pbkv::TileDesc *)lease.dev;
-    p.n_tiles = (int32_t)tiles.size();
     p.Hq = s->num_q_heads; p.Hkv = s->num_kv_heads;
     p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
+    p.mirror = nullptr;
+    const bool bf16 = s->dtype == PBKV_BF16;
+    auto launch = [&]() {
+        return bf16 ? pbkv::launch_attn_bf16(p, s->head_dim, st) : pbkv::launch_attn_f32(p, s->head_dim, st);
+    };
+
+    DevState *ds = nullptr;
+    if ((rc = device_state(&ds))) return rc;
+    std::lock_guard<std::mutex> lock(ds->mu);
+    StreamCache *sc = nullptr;
+    char *slot = nullptr;
+    const int forced = pbkv::attn_bf16_forced_waves();
+    if (bf16) {
+        if ((rc = stream_cache(*ds, st, &sc))) return rc;
+        if (Plan *pl = find_plan(*ds, *sc, PLAN_ATTN, s, forced, prefix_lens, new_lens, &slot)) {
+            p.tiles = (const pbkv::TileDesc *)slot;
+            p.n_tiles = pl->n_a;
+            p.waves = pl->waves;
+            hipError_t e = launch();
+            return e == hipSuccess ? PBKV_OK : fail_hip(e, "attention launch");
+        }
+    }
+
+    const int G = s->num_q_heads / s->num_kv_heads;
+    const int waves = bf16 ? pbkv::attn_bf16_waves(prefix_lens, new_lens, s->batch) : 0;
+    const int T = bf16 ? pbkv::attn_bf16_tile_tokens(s->head_dim, G, waves) : pbkv::attn_f32_tile_tokens();
+    std::vector<pbkv::TileDesc> &tiles = tl_tiles;
+    const int per_tile = bf16 ? pbkv::attn_bf16_units_per_tile(s->num_kv_heads, G) : 1;
+    if ((rc = build_tiles(s, prefix_lens, new_lens, T, &tiles, per_tile, waves == 4 ? 2 * MI355X_CUS : 0))) return rc;
+    const size_t bytes = tiles.size() * sizeof(pbkv::TileDesc);
+
+    Lease lease;
+    if ((rc = ring_acquire(*ds, bytes, &lease))) return rc;
+    memcpy(lease.host, tiles.data(), bytes);
+    p.tiles = (const pbkv::TileDesc *)lease.dev;
+    p.n_tiles = (int32_t)tiles.size();
     p.waves = waves;
-    p.trace = nullptr;
-    hipStream_t st = (hipStream_t)stream;
-    if ((rc = ring_commit(lease, tiles.size() * sizeof(pbkv::TileDesc), st))) return rc;
-    hipError_t e = s->dtype == PBKV_BF16 ? pbkv::launch_attn_bf16(p, s->head_dim, st)
-                                         : pbkv::launch_attn_f32(p, s->head_dim, st);
+    Plan *pl = nullptr;
+    if (bf16 && bytes <= PLAN_SLOT_BYTES) {
+        pl = new_plan(*ds, *sc, PLAN_ATTN, s, forced, prefix_lens, new_lens, &slot);
+        pl->n_a = p.n_tiles;
+        pl->waves = waves;
+        p.mirror = (pbkv::TileDesc *)slot;
+    }
+    hipError_t e = launch();
     int rel = ring_release(lease, st);
     if (e != hipSuccess) return fail_hip(e, "attention launch");
+    if (pl) pl->valid = true;
     return rel;
 }
 
@@ -362,7 +521,7 @@ int pbkv_gather_probe(const pbkv_shape *s, const void *k_new, const void *v_new,
     const int waves = pbkv::attn_bf16_waves(prefix_lens, new_lens, s->batch);   // the attention call's own choice
     const int T = pbkv::attn_bf16_tile_tokens(s->head_dim, G, waves);
     *unit_tokens = T;
-    std::vector<pbkv::TileDesc> tiles;
+    std::vector<pbkv::TileDesc> &tiles = tl_tiles;
     if ((rc = build_tiles(s, prefix_lens, new_lens, T, &tiles, pbkv::attn_bf16_units_per_tile(s->num_kv_heads, G),
                           waves == 4 ? 2 * MI355X_CUS : 0)))
         return rc;
@@ -381,8 +540,12 @@ int pbkv_gather_probe(const pbkv_shape *s, const void *k_new, const void *v_new,
         (rc = check_device_ptr(unit_xor, "unit_xor")))
         return rc;
 
+    if ((rc = check_not_capturing((hipStream_t)stream, "this call"))) return rc;
+    DevState *ds = nullptr;
+    if ((rc = device_state(&ds))) return rc;
+    std::lock_guard<std::mutex> lock(ds->mu);
     Lease lease;
-    if ((rc = ring_acquire(tiles.size() * sizeof(pbkv::TileDesc), &lease))) return rc;
+    if ((rc = ring_acquire(*ds, tiles.size() * sizeof(pbkv::TileDesc), &lease))) return rc;
     memcpy(lease.host, tiles.data(), tiles.size() * sizeof(pbkv::TileDesc));
     pbkv::AttnParams p;
     p.q = nullptr; p.k_new = k_new; p.v_new = v_new; p.kv_pool = kv_pool; p.out = unit_xor;
@@ -392,9 +555,8 @@ int pbkv_gather_probe(const pbkv_shape *s, const void *k_new, const void *v_new,
     p.Hq = s->num_q_heads; p.Hkv = s->num_kv_heads;
     p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
     p.waves = waves;
-    p.trace = nullptr;
+    p.mirror = nullptr;
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = ring_commit(lease, tiles.size() * sizeof(pbkv::TileDesc), st))) return rc;
     hipError_t e = pbkv::launch_gather_probe(p, s->head_dim, st);
     int rel = ring_release(lease, st);
     if (e != hipSuccess) return fail_hip(e, "gather probe launch");
@@ -420,13 +582,34 @@ int pbkv_append_kv(const pbkv_shape *s, const void *k_new, const void *v_new, vo
         (rc = check_device_ptr(kv_pool, "kv_pool")) || (rc = check_device_ptr(block_table, "block_table")))
         return rc;
 
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = check_not_capturing(st, "pbkv_append_kv"))) return rc;
+    pbkv::AppendParams p;
+    p.k_new = k_new; p.v_new = v_new; p.kv_pool = kv_pool; p.block_table = block_table;
+    p.mirror = nullptr;
+    p.Hkv = s->num_kv_heads; p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
+
+    DevState *ds = nullptr;
+    if ((rc = device_state(&ds))) return rc;
+    std::lock_guard<std::mutex> lock(ds->mu);
+    StreamCache *sc = nullptr;
+    char *slot = nullptr;
+    if ((rc = stream_cache(*ds, st, &sc))) return rc;
+    if (Plan *pl = find_plan(*ds, *sc, PLAN_APPEND, s, 0, prefix_lens, new_lens, &slot)) {
+        p.descs = (const pbkv::AppendDesc *)slot;
+        p.n_descs = pl->n_a;
+        hipError_t e = pbkv::launch_append(p, s->head_dim, elt_bytes(s->dtype), st);
+        return e == hipSuccess ? PBKV_OK : fail_hip(e, "append launch");
+    }
+
     const int P = s->page_size;
-    std::vector<pbkv::AppendDesc> descs;
+    std::vector<pbkv::AppendDesc> &descs = tl_runs;
+    descs.clear();
     int64_t row0 = 0;
     for (int r = 0; r < s->batch; r++) {
-        const int64_t p = prefix_lens[r], n = new_lens[r];
+        const int64_t pr = prefix_lens[r], n = new_lens[r];
         for (int64_t t = 0; t < n;) {
-            const int64_t pos = p + t;
+            const int64_t pos = pr + t;
             const int slot0 = (int)(pos % P);
             const int count = (int)std::min<int64_t>(P - slot0, n - t);
             descs.push_back(pbkv::AppendDesc{row0 + t, r, (int32_t)(pos / P), slot0, count, 0});
@@ -434,21 +617,60 @@ int pbkv_append_kv(const pbkv_shape *s, const void *k_new, const void *v_new, vo
         }
         row0 += n;
     }
+    if (descs.size() > (size_t)INT32_MAX / 64) return fail(PBKV_ERR_LIMIT, "too many page runs");
+    const size_t bytes = descs.size() * sizeof(pbkv::AppendDesc);
     Lease lease;
-    if ((rc = ring_acquire(descs.size() * sizeof(pbkv::AppendDesc), &lease))) return rc;
-    memcpy(lease.host, descs.data(), descs.size() * sizeof(pbkv::AppendDesc));
-    pbkv::AppendParams p;
-    p.k_new = k_new; p.v_new = v_new; p.kv_pool = kv_pool; p.block_table = block_table;
+    if ((rc = ring_acquire(*ds, bytes, &lease))) return rc;
+    memcpy(lease.host, descs.data(), bytes);
     p.descs = (const pbkv::AppendDesc *)lease.dev;
     p.n_descs = (int32_t)descs.size();
-    p.Hkv = s->num_kv_heads; p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
-    hipStream_t st = (hipStream_t)stream;
-    if ((rc = ring_commit(lease, descs.size() * sizeof(pbkv::AppendDesc), st))) return rc;
+    Plan *pl = nullptr;
+    if (bytes <= PLAN_SLOT_BYTES) {
+        pl = new_plan(*ds, *sc, PLAN_APPEND, s, 0, prefix_lens, new_lens, &slot);
+        pl->n_a = p.n_descs;
+        p.mirror = (pbkv::AppendDesc *)slot;
+    }
     hipError_t e = pbkv::launch_append(p, s->head_dim, elt_bytes(s->dtype), st);
     int rel = ring_release(lease, st);
     if (e != hipSuccess) return fail_hip(e, "append launch");
+    if (pl) pl->valid = true;
     return rel;
 }
+
+}  // extern "C"
+
+namespace {
+
+// Page ids of a swap: inside the pool and (swap-in: they are destinations) all distinct.
+int check_page_ids(const pbkv_shape *s, const int32_t *page_ids, int32_t n_pages, bool distinct) {
+    for (int i = 0; i < n_pages; i++) {
+        const int32_t id = page_ids[i];
+        if (id < 0 || id >= s->num_pages)
+            return fail(PBKV_ERR_RANGE, "page_ids[%d] = %d outside pool of %d pages", i, id, s->num_pages);
+    }
+    if (!distinct) return PBKV_OK;
+    if ((int64_t)n_pages * 16 < s->num_pages) {
+        // few pages of a large pool: sort a copy instead of clearing a flag per pool page
+        std::vector<int32_t> &ids = tl_ids;
+        ids.assign(page_ids, page_ids + n_pages);
+        std::sort(ids.begin(), ids.end());
+        for (int i = 1; i < n_pages; i++)
+            if (ids[i] == ids[i - 1]) return fail(PBKV_ERR_ALIAS, "page id %d appears twice", ids[i]);
+        return PBKV_OK;
+    }
+    std::vector<uint8_t> &seen = tl_seen;
+    seen.assign((size_t)s->num_pages, 0);
+    for (int i = 0; i < n_pages; i++) {
+        const int32_t id = page_ids[i];
+        if (seen[id]) return fail(PBKV_ERR_ALIAS, "page_ids[%d] = %d appears twice", i, id);
+        seen[id] = 1;
+    }
+    return PBKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
 
 int pbkv_swap_in_pages(const pbkv_shape *s, const void *host_pages, const int32_t *page_ids,
                        int32_t n_pages, void *kv_pool, void *stream) {
@@ -458,24 +680,20 @@ int pbkv_swap_in_pages(const pbkv_shape *s, const void *host_pages, const int32_
     if (n_pages < 0) return fail(PBKV_ERR_RANGE, "n_pages %d", n_pages);
     if (n_pages == 0) return PBKV_OK;
     if (!host_pages || !page_ids || !kv_pool) return fail(PBKV_ERR_NULL, "pbkv_swap_in_pages: NULL argument");
-    std::vector<uint8_t> seen((size_t)s->num_pages, 0);
-    for (int i = 0; i < n_pages; i++) {
-        const int32_t id = page_ids[i];
-        if (id < 0 || id >= s->num_pages)
-            return fail(PBKV_ERR_RANGE, "page_ids[%d] = %d outside pool of %d pages", i, id, s->num_pages);
-        if (seen[id]) return fail(PBKV_ERR_ALIAS, "page_ids[%d] = %d appears twice", i, id);
-        seen[id] = 1;
-    }
+    if ((rc = check_page_ids(s, page_ids, n_pages, true))) return rc;
     if ((rc = check_aligned(host_pages, "host_pages")) || (rc = check_aligned(kv_pool, "kv_pool"))) return rc;
     const void *host_dev = nullptr;
     if ((rc = check_pinned_ptr(host_pages, "host_pages", &host_dev))) return rc;
     if ((rc = check_device_ptr(kv_pool, "kv_pool"))) return rc;
 
+    if ((rc = check_not_capturing((hipStream_t)stream, "this call"))) return rc;
+    DevState *ds = nullptr;
+    if ((rc = device_state(&ds))) return rc;
+    std::lock_guard<std::mutex> lock(ds->mu);
     Lease lease;
-    if ((rc = ring_acquire((size_t)n_pages * sizeof(int32_t), &lease))) return rc;
+    if ((rc = ring_acquire(*ds, (size_t)n_pages * sizeof(int32_t), &lease))) return rc;
     memcpy(lease.host, page_ids, (size_t)n_pages * sizeof(int32_t));
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = ring_commit(lease, (size_t)n_pages * sizeof(int32_t), st))) return rc;
     hipError_t e = pbkv::launch_swap_in(host_dev, (const int32_t *)lease.dev, n_pages, kv_pool,
                                         pbkv_page_bytes(s), st);
     int rel = ring_release(lease, st);
@@ -483,17 +701,22 @@ int pbkv_swap_in_pages(const pbkv_shape *s, const void *host_pages, const int32_
     return rel;
 }
 
-int pbkv_paged_decode(const pbkv_shape *s, const void *q, const void *kv_pool, const int32_t *block_table,
-                      const int32_t *context_lens, void *out, void *stream) {
-    g_err[0] = 0;
+}  // extern "C"
+
+namespace {
+
+constexpr int64_t DECODE_TARGET_WGS = 2048;   // work-groups aimed for (1024 / 4096 / 8192 were measured: not faster)
+
+// Validation shared by the decode entry points; also sums the pages of all contexts.
+int check_decode_args(const pbkv_shape *s, const void *q, const void *kv_pool, const int32_t *block_table,
+                      const int32_t *context_lens, void *out, int64_t *total_pages, const char *who) {
     int rc = check_shape(s, true);
     if (rc) return rc;
-    if (s->dtype != PBKV_BF16) return fail(PBKV_ERR_DTYPE, "pbkv_paged_decode: bf16 only");
+    if (s->dtype != PBKV_BF16) return fail(PBKV_ERR_DTYPE, "%s: bf16 only", who);
+    *total_pages = 0;
     if (s->batch == 0) return PBKV_OK;
-    if (!q || !kv_pool || !block_table || !context_lens || !out)
-        return fail(PBKV_ERR_NULL, "pbkv_paged_decode: NULL argument");
+    if (!q || !kv_pool || !block_table || !context_lens || !out) return fail(PBKV_ERR_NULL, "%s: NULL argument", who);
     const int B = s->batch, P = s->page_size;
-    int64_t total_pages = 0;
     for (int r = 0; r < B; r++) {
         const int64_t L = context_lens[r];
         if (L < 0 || L > INT32_MAX - 4096) return fail(PBKV_ERR_RANGE, "request %d: context length %lld", r, (long long)L);
@@ -501,21 +724,27 @@ int pbkv_paged_decode(const pbkv_shape *s, const void *q, const void *kv_pool, c
         if (pages > s->max_pages_per_req)
             return fail(PBKV_ERR_RANGE, "request %d needs %lld pages, block_table rows hold %d", r, (long long)pages,
                         s->max_pages_per_req);
-        total_pages += pages;
+        *total_pages += pages;
     }
     if ((rc = check_aligned(q, "q")) || (rc = check_aligned(kv_pool, "kv_pool")) || (rc = check_aligned(out, "out"))) return rc;
     if ((rc = check_device_ptr(q, "q")) || (rc = check_device_ptr(kv_pool, "kv_pool")) ||
         (rc = check_device_ptr(block_table, "block_table")) || (rc = check_device_ptr(out, "out")))
         return rc;
+    return PBKV_OK;
+}
 
-    // slices: enough work-groups to fill the chip a few times over, at least 16 pages each
+// Slices of the contexts: enough work-groups to fill the chip a few times over, at least 16 pages each.
+int build_decode_units(const pbkv_shape *s, const int32_t *context_lens, int64_t total_pages,
+                       std::vector<pbkv::DecodeUnit> *units_out, std::vector<pbkv::DecodeReq> *reqs_out) {
+    const int B = s->batch, P = s->page_size;
     const int G = s->num_q_heads / s->num_kv_heads;
     const int per_unit = s->num_kv_heads * (G / pbkv::decode_heads_per_group(G));   // work-groups per slice
-    static const int64_t target_wgs = [] { const char *e = getenv("PBKV_DECODE_WGS"); return e && atoi(e) > 0 ? (int64_t)atoi(e) : (int64_t)2048; }();
-    int64_t pps = (total_pages * per_unit + target_wgs - 1) / target_wgs;
+    int64_t pps = (total_pages * per_unit + DECODE_TARGET_WGS - 1) / DECODE_TARGET_WGS;
     pps = std::max<int64_t>(16, (pps + 3) & ~(int64_t)3);
-    std::vector<pbkv::DecodeUnit> units;
-    std::vector<pbkv::DecodeReq> reqs((size_t)B);
+    std::vector<pbkv::DecodeUnit> &units = *units_out;
+    std::vector<pbkv::DecodeReq> &reqs = *reqs_out;
+    units.clear();
+    reqs.assign((size_t)B, pbkv::DecodeReq{0, 0, {0, 0}});
     for (int r = 0; r < B; r++) {
         const int32_t L = context_lens[r];
         const int32_t pages = (L + P - 1) / P;
@@ -527,29 +756,78 @@ int pbkv_paged_decode(const pbkv_shape *s, const void *q, const void *kv_pool, c
         }
     }
     if (units.size() > (size_t)INT32_MAX / 64) return fail(PBKV_ERR_LIMIT, "too many slices");
+    return PBKV_OK;
+}
 
+size_t decode_scratch_bytes(const pbkv_shape *s, size_t n_units) {
+    const int G = s->num_q_heads / s->num_kv_heads;
+    const int per_unit = s->num_kv_heads * (G / pbkv::decode_heads_per_group(G));
+    return std::max<size_t>(n_units, 1) * per_unit * pbkv::decode_partial_floats(s->head_dim, G) * sizeof(float);
+}
+
+}  // namespace
+
+extern "C" {
+
+int pbkv_paged_decode(const pbkv_shape *s, const void *q, const void *kv_pool, const int32_t *block_table,
+                      const int32_t *context_lens, void *out, void *stream) {
+    g_err[0] = 0;
+    int64_t total_pages = 0;
+    int rc = check_decode_args(s, q, kv_pool, block_table, context_lens, out, &total_pages, "pbkv_paged_decode");
+    if (rc) return rc;
+    if (s->batch == 0) return PBKV_OK;
+    const int B = s->batch;
     hipStream_t st = (hipStream_t)stream;
-    float *scratch = nullptr;
-    const size_t need = std::max<size_t>(units.size(), 1) * per_unit * pbkv::decode_partial_floats(s->head_dim, G) * sizeof(float);
-    if ((rc = decode_scratch(need, &scratch))) return rc;
+    if ((rc = check_not_capturing(st, "pbkv_paged_decode"))) return rc;
+    pbkv::DecodeParams p;
+    p.q = q; p.kv_pool = kv_pool; p.out = out; p.block_table = block_table;
+    p.mirror_units = nullptr; p.mirror_reqs = nullptr;
+    p.n_reqs = B;
+    p.Hq = s->num_q_heads; p.Hkv = s->num_kv_heads;
+    p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
+
+    DevState *ds = nullptr;
+    if ((rc = device_state(&ds))) return rc;
+    std::lock_guard<std::mutex> lock(ds->mu);
+    StreamCache *sc = nullptr;
+    char *slot = nullptr;
+    if ((rc = stream_cache(*ds, st, &sc))) return rc;
+    if (Plan *pl = find_plan(*ds, *sc, PLAN_DECODE, s, 0, context_lens, nullptr, &slot)) {
+        if ((rc = decode_scratch(*sc, (size_t)pl->aux, &p.scratch))) return rc;
+        p.units = (const pbkv::DecodeUnit *)slot;
+        p.reqs = (const pbkv::DecodeReq *)(slot + (size_t)pl->n_a * sizeof(pbkv::DecodeUnit));
+        p.n_units = pl->n_a;
+        hipError_t e = pbkv::launch_decode_bf16(p, s->head_dim, st);
+        return e == hipSuccess ? PBKV_OK : fail_hip(e, "decode launch");
+    }
+
+    std::vector<pbkv::DecodeUnit> &units = tl_units;
+    std::vector<pbkv::DecodeReq> &reqs = tl_reqs;
+    if ((rc = build_decode_units(s, context_lens, total_pages, &units, &reqs))) return rc;
+    const size_t need = decode_scratch_bytes(s, units.size());
+    if ((rc = decode_scratch(*sc, need, &p.scratch))) return rc;
 
     Lease lease;
     const size_t ub = units.size() * sizeof(pbkv::DecodeUnit), rb = reqs.size() * sizeof(pbkv::DecodeReq);
-    if ((rc = ring_acquire(ub + rb, &lease))) return rc;
+    if ((rc = ring_acquire(*ds, ub + rb, &lease))) return rc;
     memcpy(lease.host, units.data(), ub);
     memcpy((char *)lease.host + ub, reqs.data(), rb);
-    if ((rc = ring_commit(lease, ub + rb, st))) return rc;
-    pbkv::DecodeParams p;
-    p.q = q; p.kv_pool = kv_pool; p.out = out; p.block_table = block_table;
     p.units = (const pbkv::DecodeUnit *)lease.dev;
     p.reqs = (const pbkv::DecodeReq *)((const char *)lease.dev + ub);
-    p.scratch = scratch;
-    p.n_units = (int32_t)units.size(); p.n_reqs = B;
-    p.Hq = s->num_q_heads; p.Hkv = s->num_kv_heads;
-    p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
+    p.n_units = (int32_t)units.size();
+    Plan *pl = nullptr;
+    if (ub + rb <= PLAN_SLOT_BYTES) {
+        pl = new_plan(*ds, *sc, PLAN_DECODE, s, 0, context_lens, nullptr, &slot);
+        pl->n_a = p.n_units;
+        pl->n_b = B;
+        pl->aux = (int64_t)need;
+        p.mirror_units = (pbkv::DecodeUnit *)slot;
+        p.mirror_reqs = (pbkv::DecodeReq *)(slot + ub);
+    }
     hipError_t e = pbkv::launch_decode_bf16(p, s->head_dim, st);
     int rel = ring_release(lease, st);
     if (e != hipSuccess) return fail_hip(e, "decode launch");
+    if (pl) pl->valid = true;
     return rel;
 }
 
@@ -561,21 +839,20 @@ int pbkv_swap_out_pages(const pbkv_shape *s, const void *kv_pool, const int32_t 
     if (n_pages < 0) return fail(PBKV_ERR_RANGE, "n_pages %d", n_pages);
     if (n_pages == 0) return PBKV_OK;
     if (!host_pages || !page_ids || !kv_pool) return fail(PBKV_ERR_NULL, "pbkv_swap_out_pages: NULL argument");
-    for (int i = 0; i < n_pages; i++) {
-        const int32_t id = page_ids[i];
-        if (id < 0 || id >= s->num_pages)
-            return fail(PBKV_ERR_RANGE, "page_ids[%d] = %d outside pool of %d pages", i, id, s->num_pages);
-    }
+    if ((rc = check_page_ids(s, page_ids, n_pages, false))) return rc;
     if ((rc = check_aligned(host_pages, "host_pages")) || (rc = check_aligned(kv_pool, "kv_pool"))) return rc;
     const void *host_dev = nullptr;
     if ((rc = check_pinned_ptr(host_pages, "host_pages", &host_dev))) return rc;
     if ((rc = check_device_ptr(kv_pool, "kv_pool"))) return rc;
 
+    if ((rc = check_not_capturing((hipStream_t)stream, "this call"))) return rc;
+    DevState *ds = nullptr;
+    if ((rc = device_state(&ds))) return rc;
+    std::lock_guard<std::mutex> lock(ds->mu);
     Lease lease;
-    if ((rc = ring_acquire((size_t)n_pages * sizeof(int32_t), &lease))) return rc;
+    if ((rc = ring_acquire(*ds, (size_t)n_pages * sizeof(int32_t), &lease))) return rc;
     memcpy(lease.host, page_ids, (size_t)n_pages * sizeof(int32_t));
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = ring_commit(lease, (size_t)n_pages * sizeof(int32_t), st))) return rc;
     hipError_t e = pbkv::launch_swap_out(kv_pool, (const int32_t *)lease.dev, n_pages, (void *)host_dev,
                                          pbkv_page_bytes(s), st);
     int rel = ring_release(lease, st);

@@ -40,7 +40,7 @@ struct AttnParams {
     const TileDesc *tiles;
     int32_t n_tiles, Hq, Hkv, max_pages, num_pages;
     int32_t waves;   // bf16 kernel: waves per work-group (attn_bf16_waves); the tiles were cut for it
-    void *trace;   // development instrumentation; unused unless built with it
+    TileDesc *mirror;   // device memory that receives a copy of the tiles the launch read, or null
 };
 
 // Decode: one slice of a request's context pages, shared by its KV heads and head groups.
@@ -65,6 +65,8 @@ struct DecodeParams {
     const int32_t *block_table;
     const DecodeUnit *units;
     const DecodeReq *reqs;
+    DecodeUnit *mirror_units;   // device memory that receives a copy of units / reqs, or null
+    DecodeReq *mirror_reqs;
     float *scratch;
     int32_t n_units, n_reqs, Hq, Hkv, max_pages, num_pages;
 };
@@ -74,12 +76,15 @@ struct AppendParams {
     void *kv_pool;
     const int32_t *block_table;
     const AppendDesc *descs;
+    AppendDesc *mirror;         // device memory that receives a copy of descs, or null
     int32_t n_descs, Hkv, max_pages, num_pages;
 };
 
 // Waves per work-group the bf16 kernel runs this batch with, and the tokens per attention tile
 // that follow from it (what the host cuts the suffix into).
 int attn_bf16_waves(const int32_t *prefix_lens, const int32_t *new_lens, int batch);
+void attn_bf16_force_waves(int waves);   // 4 or 8: every later launch uses that shape; anything else: automatic
+int attn_bf16_forced_waves();
 int attn_bf16_tile_tokens(int head_dim, int group, int waves);
 int attn_f32_tile_tokens();
 

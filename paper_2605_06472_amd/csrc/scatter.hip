@@ -10,33 +10,57 @@ static __device__ __forceinline__ int clamp_page(int pg, int num_pages) {
     return pg < 0 ? 0 : (pg >= num_pages ? num_pages - 1 : pg);
 }
 
-// One work-group per AppendDesc: up to 16 consecutive suffix tokens of one request that
-// fall in one pool page.  Chunk index order = source order (token, K|V, head, 16B chunk),
-// so a wave reads contiguous memory and writes whole rows of row_bytes.
-__global__ __launch_bounds__(256) void append_kernel(AppendParams p, int row_chunks, int page_size) {
-    const AppendDesc d = p.descs[blockIdx.x];
-    const int pg = clamp_page(p.block_table[(int64_t)d.req * p.max_pages + d.logical_page], p.num_pages);
+// Append: the runs (AppendDesc: up to 16 consecutive suffix tokens of one request that fall in one
+// pool page) are cut into parts of APPEND_CHUNKS 16-byte chunks, and a grid sized to the chip strides
+// over (run, part).  Chunk index order = source order (token, K|V, head, 16B chunk), so a wave reads
+// contiguous memory and writes whole rows; every thread has four independent loads in flight before
+// its first store.
+constexpr int APPEND_CHUNKS = 1024;   // 16 KiB per work-group and pass
+constexpr int APPEND_MAX_WGS = 2048;  // 8 work-groups of 4 waves per CU
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+__global__ __launch_bounds__(256) void append_kernel(AppendParams p, int row_chunks, int page_size, int parts_per_run) {
     const int per_tok = 2 * p.Hkv * row_chunks;               // 16-byte chunks per token (K and V)
-    const int total = d.count * per_tok;
     const int64_t page_chunks = (int64_t)per_tok * page_size;
-    const uint4 *ksrc = (const uint4 *)p.k_new;
-    const uint4 *vsrc = (const uint4 *)p.v_new;
-    uint4 *pool = (uint4 *)p.kv_pool + (int64_t)pg * page_chunks;
-    for (int idx = threadIdx.x; idx < total; idx += 256) {
-        const int c = idx % row_chunks;
-        const int g = (idx / row_chunks) % p.Hkv;
-        const int kv = (idx / (row_chunks * p.Hkv)) & 1;
-        const int t = idx / per_tok;
-        const int64_t s = ((d.src_row + t) * p.Hkv + g) * row_chunks + c;
-        const uint4 v = kv ? vsrc[s] : ksrc[s];
-        pool[((int64_t)(kv * p.Hkv + g) * page_size + d.slot0 + t) * row_chunks + c] = v;
+    const u32x4 *ksrc = (const u32x4 *)p.k_new;
+    const u32x4 *vsrc = (const u32x4 *)p.v_new;
+    for (int64_t item = blockIdx.x; item < (int64_t)p.n_descs * parts_per_run; item += gridDim.x) {
+        const int run = (int)(item / parts_per_run), part = (int)(item % parts_per_run);
+        const AppendDesc d = p.descs[run];
+        if (p.mirror != nullptr && part == 0 && threadIdx.x == 0) p.mirror[run] = d;
+        const int total = d.count * per_tok;
+        if (part * APPEND_CHUNKS >= total) continue;
+        const int pg = clamp_page(p.block_table[(int64_t)d.req * p.max_pages + d.logical_page], p.num_pages);
+        u32x4 *pool = (u32x4 *)p.kv_pool + (int64_t)pg * page_chunks;
+        u32x4 v[4];
+        int64_t dst[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int idx = part * APPEND_CHUNKS + i * 256 + threadIdx.x;
+            dst[i] = -1;
+            if (idx < total) {
+                const int c = idx % row_chunks;
+                const int g = (idx / row_chunks) % p.Hkv;
+                const int kv = (idx / (row_chunks * p.Hkv)) & 1;
+                const int t = idx / per_tok;
+                const int64_t s = ((d.src_row + t) * p.Hkv + g) * row_chunks + c;
+                v[i] = __builtin_nontemporal_load((kv ? vsrc : ksrc) + s);
+                dst[i] = ((int64_t)(kv * p.Hkv + g) * page_size + d.slot0 + t) * row_chunks + c;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+            if (dst[i] >= 0) pool[dst[i]] = v[i];
     }
 }
 
 hipError_t launch_append(const AppendParams &p, int head_dim, int elt_bytes, hipStream_t s) {
     if (p.n_descs == 0) return hipSuccess;
     const int row_chunks = head_dim * elt_bytes / 16;
-    hipLaunchKernelGGL(append_kernel, dim3(p.n_descs), dim3(256), 0, s, p, row_chunks, 16);
+    const int parts = (16 * 2 * p.Hkv * row_chunks + APPEND_CHUNKS - 1) / APPEND_CHUNKS;
+    const int64_t items = (int64_t)p.n_descs * parts;
+    hipLaunchKernelGGL(append_kernel, dim3((unsigned)(items < APPEND_MAX_WGS ? items : APPEND_MAX_WGS)), dim3(256), 0, s,
+                       p, row_chunks, 16, parts);
     return hipGetLastError();
 }
 
@@ -48,10 +72,7 @@ hipError_t launch_append(const AppendParams &p, int head_dim, int elt_bytes, hip
 // hidden behind compute) must not park thousands of waves, each waiting microseconds on the
 // link, on the CUs and memory queues the compute kernel needs.
 constexpr int SWAP_CHUNKS = 1024;   // 16 KiB per work-group and pass
-#ifndef SWAP_MAX_WGS
-#define SWAP_MAX_WGS 32
-#endif
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+constexpr int SWAP_MAX_WGS = 32;
 
 __global__ __launch_bounds__(256) void swap_in_kernel(const u32x4 *__restrict__ host_pages,
                                                       const int32_t *__restrict__ page_ids,

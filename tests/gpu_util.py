@@ -60,15 +60,37 @@ class DeviceBatch:
         return W.to_f64(to_numpy(self.out if out is None else out))
 
 
-def sample_rows(b: W.Batch, per_request=6, tile=64, seed=0):
-    """Packed row indices: first, last, tile-boundary and random rows of every request."""
+def attention_unit(db):
+    """Suffix tokens per work unit of the attention launch this batch will get (asked of the
+    library through the size query of the gather diagnostic; 0 for fp32 batches)."""
+    b = db.b
+    if b.dtype != "bf16":
+        return 0
+    return binding.gather_probe(db.shape, db.k_new, db.v_new, db.kv_pool, db.block_table,
+                                b.prefix_lens, b.new_lens, None)[1]
+
+
+def sample_rows(b: W.Batch, per_request=6, unit=64, seed=0, max_boundaries=24):
+    """Packed row indices: first and last row, the rows on both sides of boundaries between work
+    units of `unit` suffix tokens (all of them up to max_boundaries, else a seeded choice that
+    keeps the first and the last), the rows around the 32-token sub-blocks of the first and last
+    unit, and per_request random rows of every request."""
     rng = np.random.default_rng(seed)
+    unit = unit or 64
     rows, off = [], 0
     for r in range(b.B):
         n = int(b.new_lens[r])
         if n:
-            cand = {0, n - 1, min(tile - 1, n - 1), min(tile, n - 1), (n // tile) * tile - 1 if n >= tile else 0,
-                    min((n // tile) * tile, n - 1)}
+            cand = {0, n - 1}
+            bounds = list(range(unit, n, unit))
+            if len(bounds) > max_boundaries:
+                keep = rng.choice(len(bounds) - 2, max_boundaries - 2, replace=False) + 1
+                bounds = [bounds[0], bounds[-1]] + [bounds[int(i)] for i in keep]
+            for x in bounds:
+                cand.update((x - 1, x))
+            for x in (31, 32, (n - 1) // unit * unit + 31, (n - 1) // unit * unit + 32):
+                if 0 <= x < n:
+                    cand.add(x)
             cand.update(int(x) for x in rng.integers(0, n, per_request))
             rows.extend(off + c for c in sorted(cand))
         off += n
@@ -76,10 +98,20 @@ def sample_rows(b: W.Batch, per_request=6, tile=64, seed=0):
 
 
 TOL = {"bf16": (2e-2, 1e-2), "f32": (1e-5, 1e-5)}    # (max abs error, relative L2 error)
+# The stress runs with Q scaled x8 (peaked softmax, outputs of order 1) get twice the absolute
+# bound.  The kernel folds log2(e)/sqrt(d) into Q and rounds the product once to bf16; that moves a
+# score by sigma = 2^-9/sqrt(3) * |c q * k|_2, about 0.0065 log2 units at x8 (0.0008 at x1), and in a
+# softmax that two keys dominate an output moves by up to ln2 * |delta_1 - delta_2| * 1/4 * |v_1 - v_2|,
+# about 0.03 for a 5-sigma pair and |v_1 - v_2| = 4.  A CPU emulation of the kernel's roundings on
+# 96 rows of the long-history batch gives 1.2e-2 with that rounding and 6e-3 without it (then the
+# final rounding of outputs near 3 is what is left); over the 3.5 million elements the test compares
+# the tail reaches 2.0e-2.  The relative L2 bound is the same as for the plain runs.
+PEAKED_ATOL = 4e-2
 
 
-def assert_close(got, want, dtype, what=""):
-    atol, rtol = TOL[dtype]
+def assert_close(got, want, dtype, what="", atol=None):
+    atol0, rtol = TOL[dtype]
+    atol = atol0 if atol is None else atol
     err = np.abs(got - want).max()
     rel = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-300)
     assert np.isfinite(got).all(), what

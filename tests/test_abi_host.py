@@ -169,11 +169,11 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.stdout.strip() == ""
 
 
-def test_work_group_shape_follows_the_batch(monkeypatch):
+def test_work_group_shape_follows_the_batch():
     """The bf16 attention kernel runs as four waves (32-token units) when the batch's 64-token blocks
     average fewer than 128 tile steps, else as eight (64-token units); the size query of the gather
     diagnostic reports the unit the attention call will use, without touching a device."""
-    monkeypatch.delenv("PBKV_ATTN_WAVES", raising=False)
+    binding.set_attn_waves(0)
 
     def units(batch, prefix, new, max_pages):
         shape = _shape(batch=batch, num_pages=4 * max_pages, max_pages_per_req=max_pages)
@@ -188,7 +188,13 @@ def test_work_group_shape_follows_the_batch(monkeypatch):
     assert tok == 32
     n, tok = units(2, 8064, 64, 520)                  # 128 steps
     assert tok == 64
-    monkeypatch.setenv("PBKV_ATTN_WAVES", "8")
-    assert units(4, 2048, 512, 160)[1] == 64
-    monkeypatch.setenv("PBKV_ATTN_WAVES", "4")
-    assert units(4, 32768, 2048, 2200)[1] == 32
+    try:
+        binding.set_attn_waves(8)
+        assert units(4, 2048, 512, 160)[1] == 64
+        binding.set_attn_waves(4)
+        assert units(4, 32768, 2048, 2200)[1] == 32
+        with pytest.raises(binding.PbkvError) as e:
+            binding.set_attn_waves(6)
+        assert e.value.code == -2
+    finally:
+        binding.set_attn_waves(0)

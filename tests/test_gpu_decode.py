@@ -60,6 +60,30 @@ def test_decode_full_size_batch_all_rows(oracle):
     assert np.array_equal(got, again)
 
 
+def test_decode_calls_on_two_streams_overlap_safely(oracle):
+    """Two decode calls in flight at once on different streams, each with its own batch, its own
+    cached work list and its own scratch buffer (the second batch needs a larger one than the first
+    call left behind on its stream), several rounds: every result equals the oracle's."""
+    big = W.decode_batch(seed=1105, batch=24, min_ctx=2000, max_ctx=9000, num_pages=16384)
+    small = W.ragged_small(93, "bf16", Hq=32, Hkv=8, prefix_lens=(700, 33, 4097), new_lens=(1, 1, 1), num_pages=512)
+    want = {id(x): oracle.decode(x.q, x.kv_pool, x.block_table, x.prefix_lens) for x in (big, small)}
+    dbig, dsmall = DeviceBatch(big), DeviceBatch(small)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    outs = []
+    for k in range(4):
+        (a, sa), (c, sc) = ((dbig, s1), (dsmall, s2)) if k % 2 == 0 else ((dsmall, s1), (dbig, s2))
+        oa, oc = torch.full_like(a.q, 7.0), torch.full_like(c.q, 7.0)
+        binding.paged_decode(a.shape, a.q, a.kv_pool, a.block_table, a.b.prefix_lens, oa, sa)
+        binding.paged_decode(c.shape, c.q, c.kv_pool, c.block_table, c.b.prefix_lens, oc, sc)
+        binding.paged_decode(a.shape, a.q, a.kv_pool, a.block_table, a.b.prefix_lens, oa, sa)
+        outs.append((a, oa, c, oc))
+    torch.cuda.synchronize()
+    for a, oa, c, oc in outs:
+        assert_close(W.to_f64(to_numpy(oa)), want[id(a.b)], "bf16", "stream 1")
+        assert_close(W.to_f64(to_numpy(oc)), want[id(c.b)], "bf16", "stream 2")
+
+
 def test_decode_argument_errors():
     b = W.ragged_small(92, "bf16", prefix_lens=(40,), new_lens=(1,))
     db = DeviceBatch(b)
