@@ -26,14 +26,29 @@ PEAK_HBM_GBS = 8000.0
 
 
 def _profile_traffic(workload):
-    """HBM bytes per attention launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-    as recorded in the committed profile summary for this workload; None if absent."""
-    path = os.path.join(ROOT, "profiles", "attn_bf16_%s_pmc.txt" % workload)
+    """HBM bytes per attention launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE).  This
+    run does not measure them: the figure is read from the committed profile summary of the same
+    command for this workload (None if there is none), and the line says so."""
+    rel = "profiles/attn_bf16_%s_pmc.txt" % workload
     try:
-        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
-        return float(m.group(1)) if m else None
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(os.path.join(ROOT, rel)).read(), re.M)
+        return (float(m.group(1)), "read from %s (rocprofv3 --pmc run of this command), not measured by this run" % rel) \
+            if m else (None, None)
     except OSError:
-        return None
+        return None, None
+
+
+_SIDE = None
+
+
+def side_stream(torch):
+    """The ONE side stream of this process.  Streams map onto a few hardware queues (4 per process
+    on this machine) in creation order, so a stream made late can land on the main stream's queue and
+    then runs behind it instead of beside it; this one is created first and used for every overlap."""
+    global _SIDE
+    if _SIDE is None:
+        _SIDE = torch.cuda.Stream()
+    return _SIDE
 
 
 class Step:
@@ -51,7 +66,7 @@ class Step:
         self.plp, self.nlp = vp(self.pl.ctypes.data), vp(self.nl.ctypes.data)
         self.outp = vp(db.out.data_ptr())
         self.main = torch.cuda.current_stream()
-        self.side = torch.cuda.Stream()
+        self.side = side_stream(torch)
         self.mainp, self.sidep = vp(self.main.cuda_stream), vp(self.side.cuda_stream)
         self.join_ev = torch.cuda.Event()
         self.side.wait_stream(self.main)          # inputs were produced on the main stream
@@ -83,8 +98,8 @@ class Step:
         self.main.wait_event(self.join_ev)
 
 
-def time_config(name, steps, warmup, torch, binding, W, DeviceBatch, events=True):
-    b = W.CONFIGS[name]()
+def time_config(name, steps, warmup, torch, binding, W, DeviceBatch, events=True, seed=None):
+    b = W.CONFIGS[name]() if seed is None else W.CONFIGS[name](seed=seed)
     db = DeviceBatch(b)
     if b.host_pages is not None:            # make every prefix page resident before timing attention
         db.swap_in()
@@ -122,6 +137,75 @@ def swap_in_rate(db, torch, binding, reps=3):
     return b.host_pages.nbytes / best / 1e9, best
 
 
+def append_rate(db, torch, reps=20):
+    """The paged append alone (HBM roofline: algorithmic bytes = suffix K/V read once + written once)."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(5):
+        db.append()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        db.append()
+    e1.record()
+    torch.cuda.synchronize()
+    t = e0.elapsed_time(e1) * 1e-3 / reps
+    nbytes = db.b.append_bytes()
+    return {"workload": db.b.name, "ms": t * 1e3, "bytes": nbytes,
+            "roofline": {"bound": "hbm", "kernel": "append_kernel", "achieved": nbytes / t / 1e9, "peak": PEAK_HBM_GBS,
+                         "unit": "GB/s", "frac": nbytes / t / 1e9 / PEAK_HBM_GBS}}
+
+
+def swap_rates(db, torch, binding):
+    """Swap-in and swap-out of the batch's host-tier pages against the box's own pinned copy rates."""
+    b = db.b
+    gbs, secs = swap_in_rate(db, torch, binding)
+    stage = torch.empty_like(db.host_pages, device="cuda")
+    best = None
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        stage.copy_(db.host_pages, non_blocking=True)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    del stage
+    out = {"workload": b.name, "swap_in_GBps": gbs, "swap_in_bytes": int(b.host_pages.nbytes), "swap_in_ms": secs * 1e3,
+           "pinned_h2d_memcpy_GBps": b.host_pages.nbytes / best / 1e9,
+           "swap_in_frac_of_pinned_memcpy": gbs / (b.host_pages.nbytes / best / 1e9)}
+    out.update(swap_out_rate(db, torch, binding))
+    return out
+
+
+def tiny_config(torch, binding, W, DeviceBatch, oracle, reps=200):
+    """cfg0 (the fp32 correctness configuration): time of the fp32 kernel, and the oracle on one thread."""
+    b = W.CONFIGS["cfg0"]()
+    db = DeviceBatch(b)
+    for _ in range(5):
+        db.prefill()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        db.prefill()
+    e1.record()
+    torch.cuda.synchronize()
+    gpu_ms = e0.elapsed_time(e1) / reps
+    want = None
+    n_threads = oracle.threads()
+    try:
+        oracle.set_threads(1)
+        t0 = time.perf_counter()
+        for _ in range(5):
+            want = oracle.prefill(b.q, b.k_new, b.v_new, b.kv_pool, b.block_table, b.prefix_lens, b.new_lens)
+        one = (time.perf_counter() - t0) / 5
+    finally:
+        oracle.set_threads(n_threads)
+    from tests.gpu_util import to_numpy
+    err = float(np.abs(W.to_f64(to_numpy(db.out)) - want).max())
+    return {"workload": b.name, "gpu_ms_per_call": gpu_ms, "oracle_single_thread_ms": one * 1e3,
+            "new_tokens": b.N, "max_abs_err": err}
+
+
 def overlap_schedule(db, torch, binding, groups=8, reps=3):
     """Mixed hit/miss batch end to end (Sec. 4.3: transfers hidden behind compute).  The scheduler
     orders the batch by missing pages and cuts it into groups; the side stream swaps group g+1 in (one
@@ -130,7 +214,7 @@ def overlap_schedule(db, torch, binding, groups=8, reps=3):
     of the first swap-in to completion of the last attention and append.  The back-to-back order
     runs one swap-in, one attention and one append call for the whole batch."""
     b = db.b
-    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    main, side = torch.cuda.current_stream(), side_stream(torch)
     order = np.argsort(np.diff(b.swap_offsets), kind="stable")
     off = np.concatenate([[0], np.cumsum(b.new_lens)]).astype(np.int64)
     # the batch in scheduler order: packed rows, block-table rows and lengths permuted once, outside the clock
@@ -261,11 +345,19 @@ def prefetch_behind_decode(db, out, lens, step_alone, torch, binding, steps=10):
     if n_pages == 0:
         return {"error": "no free pages in the pool"}
     host = torch.empty((n_pages * steps,) + tuple(db.kv_pool.shape[1:]), dtype=db.kv_pool.dtype).pin_memory()
-    side = torch.cuda.Stream()
+    side = side_stream(torch)
     main = torch.cuda.current_stream()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
+    # the transfers alone, for comparison
+    s0.record(side)
+    for k in range(steps):
+        binding.swap_in_pages(db.shape, host[k * n_pages:(k + 1) * n_pages], free[k * n_pages:(k + 1) * n_pages],
+                              db.kv_pool, side)
+    s1.record(side)
+    torch.cuda.synchronize()
+    t_swap_alone = s0.elapsed_time(s1) * 1e-3 / steps
     side.wait_stream(main)
     e0.record(main)
     s0.record(side)
@@ -278,9 +370,14 @@ def prefetch_behind_decode(db, out, lens, step_alone, torch, binding, steps=10):
     torch.cuda.synchronize()
     t_dec = e0.elapsed_time(e1) * 1e-3 / steps
     t_swap = s0.elapsed_time(s1) * 1e-3 / steps
+    t_both = max(t_dec, t_swap)
     return {"pages_per_step": n_pages, "bytes_per_step": n_pages * page_bytes,
-            "decode_step_ms_alone": step_alone * 1e3, "decode_step_ms_with_prefetch": t_dec * 1e3,
-            "swap_in_ms_per_step": t_swap * 1e3, "swap_in_GBps": n_pages * page_bytes / t_swap / 1e9}
+            "decode_step_ms_alone": step_alone * 1e3, "swap_in_ms_per_step_alone": t_swap_alone * 1e3,
+            "decode_step_ms_with_prefetch": t_dec * 1e3,
+            "swap_in_ms_per_step": t_swap * 1e3, "swap_in_GBps": n_pages * page_bytes / t_swap / 1e9,
+            "back_to_back_ms": (step_alone + t_swap_alone) * 1e3,
+            "hidden_fraction_of_transfer": max(0.0, min(1.0, (step_alone + t_swap_alone - t_both) / t_swap_alone)),
+            "overlapped": bool(t_both < 0.9 * (step_alone + t_swap_alone))}
 
 
 def policy_latency(steps=6000, warm=3000, concurrency=72):
@@ -441,14 +538,55 @@ def predictor_rate(torch, W, reps=2000, n_x=32):
                                  "note": "Sec. 4.1: the paper's predictor (PyTorch, its GPUs), same batch size; widths are not published"}}
 
 
+def attention_roofline(b, name, kern_ms):
+    """Roofline object of the attention launch of one workload: exact FLOPs of the launch
+    (4 d H_q sum_r(n_r p_r + n_r(n_r+1)/2), masked upper triangle not counted) over the average of the
+    HIP-event brackets around the launches on their own stream inside the timed region."""
+    flops = b.attention_flops()
+    tf = flops / (kern_ms * 1e-3) / 1e12
+    traffic, source = _profile_traffic(name)
+    return {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": tf, "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s", "frac": tf / PEAK_BF16_TFLOPS, "flops_per_launch": flops,
+            "avg_launch_ms": kern_ms, "traffic": traffic, "traffic_source": source,
+            "algorithmic_bytes_per_launch": b.attention_bytes()}
+
+
+def oracle_baseline(b, oracle, budget_s=12.0):
+    """The oracle as it stands on this host's cores, on a bounded, evenly spaced sample of the
+    suffix rows of the same batch (all query heads of each row); rows per second of that sample
+    stand for new tokens per second of the batch."""
+    pool = b.kv_pool if b.host_pages is None else oracle.swap_in(b.host_pages, b.swap_page_ids, b.kv_pool)
+    probe = np.unique(np.linspace(0, b.N - 1, 64).astype(np.int64))
+    t0 = time.perf_counter()
+    oracle.prefill(b.q, b.k_new, b.v_new, pool, b.block_table, b.prefix_lens, b.new_lens, rows=probe)
+    per_row = (time.perf_counter() - t0) / len(probe)
+    n_rows = int(min(b.N, max(64, budget_s / per_row)))
+    rows = np.unique(np.linspace(0, b.N - 1, n_rows).astype(np.int64))
+    t0 = time.perf_counter()
+    oracle.prefill(b.q, b.k_new, b.v_new, pool, b.block_table, b.prefix_lens, b.new_lens, rows=rows)
+    dt = time.perf_counter() - t0
+    p = b.prefix_lens.astype(np.int64)
+    off = np.concatenate([[0], np.cumsum(b.new_lens)]).astype(np.int64)
+    req = np.searchsorted(off, rows, side="right") - 1
+    sample_flops = int(4 * b.d * b.Hq * np.sum(p[req] + (rows - off[req]) + 1))
+    return {"value": len(rows) / dt, "unit": "new tokens/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": "%d of %d suffix rows of %s, evenly spaced over the packed batch, all %d query heads, one "
+                      "pass, %.1f s; the sample holds %.4f of the batch's FLOPs against %.4f of its rows, so "
+                      "rows/s of the sample stand for the batch"
+                      % (len(rows), b.N, b.name, b.Hq, dt, sample_flops / b.attention_flops(), len(rows) / b.N),
+            "gflops_fp64": sample_flops / dt / 1e9}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--config", default="cfg1", choices=["cfg1", "cfg2", "cfg3", "cfg4"])
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--config", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4"],
+                    help="workload of the headline line (default: the largest one, the mixed hit/miss batch with "
+                         "its pages resident)")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads and the CPU baseline")
-    ap.add_argument("--part", default=None, choices=["decode", "policy", "predictor"],
+    ap.add_argument("--part", default=None, choices=["decode", "policy", "predictor", "swap", "gather", "append"],
                     help="run only this secondary measurement and print its JSON object (for profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 256 MiB device-to-device copies (known HBM traffic) so that a "
@@ -468,6 +606,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    side_stream(torch)                        # before any other stream exists
     import __graft_entry__
     __graft_entry__.ensure_built()            # compiles only if nothing is built yet
     binding.load()
@@ -489,11 +628,25 @@ def main():
     if args.part == "predictor":
         print(json.dumps(predictor_rate(torch, W)))
         return
+    if args.part == "swap":
+        db = DeviceBatch(W.CONFIGS["cfg4"]())
+        gbs, secs = swap_in_rate(db, torch, binding)
+        out = {"swap_in_GBps": gbs, "swap_in_ms": secs * 1e3, "swap_in_bytes": int(db.b.host_pages.nbytes)}
+        out.update(swap_out_rate(db, torch, binding))
+        print(json.dumps(out))
+        return
+    if args.part == "gather":
+        db = DeviceBatch(W.CONFIGS["cfg3"]())
+        print(json.dumps(gather_rate(db, torch, binding)))
+        return
+    if args.part == "append":
+        db = DeviceBatch(W.CONFIGS["cfg3"]())
+        print(json.dumps(append_rate(db, torch)))
+        return
 
     b, db, wall, kern_ms = time_config(args.config, args.steps, args.warmup, torch, binding, W, DeviceBatch)
     ms_per_step = wall / args.steps * 1e3
     flops = b.attention_flops()
-    tflops_kernel = flops / (kern_ms * 1e-3) / 1e12
     line = {
         "metric": "prefix-reuse prefill new tokens/s + TFLOP/s (MFMA util %), 8B-class GQA",
         "value": b.N / (ms_per_step * 1e-3),
@@ -504,82 +657,71 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": b.name, "batch": b.B, "new_tokens": b.N,
                    "prefix_lens": [int(b.prefix_lens.min()), int(b.prefix_lens.max())],
+                   "new_lens": [int(b.new_lens.min()), int(b.new_lens.max())],
                    "heads_q_kv": [b.Hq, b.Hkv], "head_dim": b.d, "page_size": b.P,
-                   "step": "attention (main stream) + paged append (side stream, overlapped), one layer"},
+                   "step": "attention (main stream) + paged append (side stream, overlapped), one layer, every "
+                           "prefix page resident in the pool; the host->pool swap-in of this workload and the "
+                           "overlapped schedule are timed under extra"},
         "tflops_step": flops / (ms_per_step * 1e-3) / 1e12,
         "mfma_util_step": flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-        "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": tflops_kernel,
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops_kernel / PEAK_BF16_TFLOPS,
-                     "flops_per_launch": flops, "avg_launch_ms": kern_ms,
-                     "traffic": _profile_traffic(args.config),
-                     "algorithmic_bytes_per_launch": b.attention_bytes()},
+        "roofline": attention_roofline(b, args.config, kern_ms),
         "paper_context": "PBKV end-to-end workflow latency 1.85x vs LRU and 1.26x vs KVFlow on 8x A6000 "
                          "(SGLang + HiCache, Qwen3-14B/32B); cache-policy numbers, not a kernel baseline",
     }
 
     if not args.no_extra:
         import oracle
-        # CPU baseline: the oracle as it stands on this host's cores, bounded sample of the same workload
-        rows_all = np.arange(b.N, dtype=np.int64)
-        probe = np.linspace(0, b.N - 1, 32).astype(np.int64)
-        t0 = time.perf_counter()
-        oracle.prefill(b.q, b.k_new, b.v_new, b.kv_pool, b.block_table, b.prefix_lens, b.new_lens, rows=probe)
-        per_row = (time.perf_counter() - t0) / len(probe)
-        n_rows = int(min(b.N, max(32, 15.0 / per_row)))
-        rows = rows_all if n_rows == b.N else np.unique(np.linspace(0, b.N - 1, n_rows).astype(np.int64))
-        reps, dt = 0, 0.0
-        while dt < 10.0:                                    # the sample repeated until ~10 s of CPU work
-            t0 = time.perf_counter()
-            oracle.prefill(b.q, b.k_new, b.v_new, b.kv_pool, b.block_table, b.prefix_lens, b.new_lens, rows=rows)
-            dt += time.perf_counter() - t0
-            reps += 1
-        line["cpu_baseline"] = {"value": len(rows) * reps / dt, "unit": "new tokens/s", "cores": oracle.threads(),
-                                "kind": "oracle",
-                                "sample": "%d of %d suffix rows (evenly spaced, all %d query heads) of %s, %d passes, %.1f s"
-                                          % (len(rows), b.N, b.Hq, b.name, reps, dt)}
+        line["cpu_baseline"] = oracle_baseline(b, oracle)
         extra = {}
+        rooflines = {args.config: dict(line["roofline"], ms_per_step=ms_per_step, new_tokens=b.N,
+                                       new_tokens_per_s=line["value"], steps=args.steps, warmup=args.warmup)}
         try:
-            _, dbn, walln, _ = time_config(args.config, args.steps, args.warmup, torch, binding, W, DeviceBatch, events=False)
-            extra["same_steps_without_event_packets"] = {"ms_per_step": walln / args.steps * 1e3,
-                                                         "new_tokens_per_s": b.N / (walln / args.steps)}
-            del dbn
-        except Exception as e:
-            extra["same_steps_without_event_packets"] = {"error": repr(e)}
-        for name in ("cfg2", "cfg3", "cfg4"):
+            extra["append"] = append_rate(db, torch)
+            if b.host_pages is not None:
+                extra["swap"] = swap_rates(db, torch, binding)
+                extra["overlap_schedule"] = overlap_schedule(db, torch, binding)
+        except Exception as e:                          # the headline line must still print
+            extra["append"] = {"error": repr(e)}
+        del db
+        torch.cuda.empty_cache()
+        for name, steps in (("cfg1", 200), ("cfg2", 60), ("cfg3", 20), ("cfg4", 20)):
             if name == args.config:
                 continue
             try:
-                steps = 20 if name == "cfg2" else 5
-                b2, db2, wall2, k2 = time_config(name, steps, 2, torch, binding, W, DeviceBatch)
-                f2 = b2.attention_flops()
-                extra[name] = {"workload": b2.name, "new_tokens": b2.N, "ms_per_step": wall2 / steps * 1e3,
-                               "new_tokens_per_s": b2.N / (wall2 / steps),
-                               "attn_kernel_ms": k2, "attn_tflops": f2 / (k2 * 1e-3) / 1e12,
-                               "attn_frac_of_bf16_peak": f2 / (k2 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+                b2, db2, wall2, k2 = time_config(name, steps, 8, torch, binding, W, DeviceBatch)
+                rooflines[name] = dict(attention_roofline(b2, name, k2), ms_per_step=wall2 / steps * 1e3,
+                                       new_tokens=b2.N, new_tokens_per_s=b2.N / (wall2 / steps), steps=steps, warmup=8)
+                if name == "cfg1":
+                    _, dbn, walln, _ = time_config(name, steps, 8, torch, binding, W, DeviceBatch, events=False)
+                    rooflines[name]["ms_per_step_without_event_packets"] = walln / steps * 1e3
+                    del dbn
                 if name == "cfg3":
-                    extra[name].update(gather_rate(db2, torch, binding))
-                if b2.host_pages is not None:
-                    gbs, secs = swap_in_rate(db2, torch, binding)
-                    # the box's own pinned host->device copy rate for the same buffer, as the ceiling
-                    stage = torch.empty_like(db2.host_pages, device="cuda")
-                    best = None
-                    for _ in range(3):
-                        torch.cuda.synchronize()
-                        t0 = time.perf_counter()
-                        stage.copy_(db2.host_pages, non_blocking=True)
-                        torch.cuda.synchronize()
-                        dt = time.perf_counter() - t0
-                        best = dt if best is None else min(best, dt)
-                    del stage
-                    extra[name].update({"swap_in_GBps": gbs, "swap_in_bytes": int(b2.host_pages.nbytes),
-                                        "swap_in_ms": secs * 1e3,
-                                        "pinned_h2d_memcpy_GBps": b2.host_pages.nbytes / best / 1e9})
-                    extra[name].update(swap_out_rate(db2, torch, binding))
-                    extra[name]["overlap_schedule"] = overlap_schedule(db2, torch, binding)
+                    extra["gather"] = gather_rate(db2, torch, binding)
+                if b2.host_pages is not None and "swap" not in extra:
+                    extra["swap"] = swap_rates(db2, torch, binding)
+                    extra["overlap_schedule"] = overlap_schedule(db2, torch, binding)
                 del db2, b2
                 torch.cuda.empty_cache()
-            except Exception as e:                      # the headline line must still print
-                extra[name] = {"error": repr(e)}
+            except Exception as e:
+                rooflines[name] = {"error": repr(e)}
+        line["rooflines"] = rooflines
+        # spread over seeds: the headline workload drawn again with seed + 100 and + 200
+        try:
+            seeds = {}
+            base_seed = {"cfg1": 1001, "cfg2": 1002, "cfg3": 1003, "cfg4": 1004}[args.config]
+            for ds in (100, 200):
+                bs, dbs, walls, ks = time_config(args.config, 10, 5, torch, binding, W, DeviceBatch, seed=base_seed + ds)
+                seeds[str(base_seed + ds)] = {"new_tokens": bs.N, "new_tokens_per_s": bs.N / (walls / 10),
+                                              "attn_frac_of_bf16_peak": bs.attention_flops() / (ks * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+                del dbs, bs
+                torch.cuda.empty_cache()
+            extra["seeds"] = seeds
+        except Exception as e:
+            extra["seeds"] = {"error": repr(e)}
+        try:
+            extra["cfg0"] = tiny_config(torch, binding, W, DeviceBatch, oracle)
+        except Exception as e:
+            extra["cfg0"] = {"error": repr(e)}
         try:
             extra["decode"] = decode_rate(torch, binding, W, DeviceBatch)
         except Exception as e:

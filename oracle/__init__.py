@@ -18,26 +18,34 @@ _LIB = None
 
 
 def _bind(path):
-    if path:
-        lib = ctypes.CDLL(path)
-        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
-        lib.pbkv_oracle_prefill.restype = ctypes.c_int
-        lib.pbkv_oracle_prefill.argtypes = [i32, i32, i32, i32, i32, i32, i64, i32,
-                                            vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, vp]
-        lib.pbkv_oracle_append.restype = ctypes.c_int
-        lib.pbkv_oracle_append.argtypes = [i32, i32, i32, i32, i32, i64, i32,
-                                           vp, vp, vp, vp, vp, vp]
-        lib.pbkv_oracle_swap_in.restype = ctypes.c_int
-        lib.pbkv_oracle_swap_in.argtypes = [i64, i64, vp, vp, i64, vp]
-        lib.pbkv_oracle_swap_out.restype = ctypes.c_int
-        lib.pbkv_oracle_swap_out.argtypes = [i64, i64, vp, vp, i64, vp]
-        lib.pbkv_oracle_threads.restype = ctypes.c_int
+    if not path:
+        raise ImportError("the oracle library is not built (oracle/build.py)")
+    lib = ctypes.CDLL(path)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+    lib.pbkv_oracle_prefill.restype = ctypes.c_int
+    lib.pbkv_oracle_prefill.argtypes = [i32, i32, i32, i32, i32, i32, i64, i32,
+                                        vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, vp]
+    lib.pbkv_oracle_append.restype = ctypes.c_int
+    lib.pbkv_oracle_append.argtypes = [i32, i32, i32, i32, i32, i64, i32,
+                                       vp, vp, vp, vp, vp, vp]
+    lib.pbkv_oracle_swap_in.restype = ctypes.c_int
+    lib.pbkv_oracle_swap_in.argtypes = [i64, i64, vp, vp, i64, vp]
+    lib.pbkv_oracle_swap_out.restype = ctypes.c_int
+    lib.pbkv_oracle_swap_out.argtypes = [i64, i64, vp, vp, i64, vp]
+    lib.pbkv_oracle_threads.restype = ctypes.c_int
+    lib.pbkv_oracle_set_threads.restype = None
+    lib.pbkv_oracle_set_threads.argtypes = [ctypes.c_int]
     return lib
 
 
 def threads():
     """Host threads the oracle's row loop uses."""
     return int(_lib().pbkv_oracle_threads())
+
+
+def set_threads(n):
+    """Host threads the row loop uses from now on (results do not depend on it)."""
+    _lib().pbkv_oracle_set_threads(int(n))
 
 
 def _lib():

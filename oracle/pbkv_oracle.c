@@ -38,6 +38,17 @@
 
 enum { ORACLE_BF16 = 0, ORACLE_F32 = 1 };
 
+/* Sets the number of threads of the row loop (the benchmark times the tiny configuration on one
+ * thread); no effect on any result: rows are independent and each is summed by one thread. */
+void pbkv_oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 /* Threads the row loop of pbkv_oracle_prefill runs on (rows are independent). */
 int pbkv_oracle_threads(void)
 {
