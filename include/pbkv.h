@@ -159,6 +159,23 @@ int pbkv_paged_decode(const pbkv_shape *shape, const void *q, const void *kv_poo
                       void *stream);
 
 /*
+ * pbkv_paged_decode for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same result bit for bit
+ * (the same kernels and the same slicing of the contexts), but the partial results of the context
+ * slices and the work lists live in one device array that is part of the library's image (8 MiB +
+ * 192 KiB per GPU, held until the process ends) and the lists reach it through kernel arguments:
+ * the call allocates nothing, records no event and copies nothing, so it may also be captured.
+ * Limits: at most 4096 requests, 4096 context slices (about 2048 / (work-groups per slice) plus one
+ * per request) and 8 MiB of partial results (520 floats per slice, KV head and group of eight query
+ * heads at d = 128 and a head ratio of 4); beyond them PBKV_ERR_LIMIT and nothing is enqueued.
+ * Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two
+ * threads) race and give wrong results; nothing in it has to be cleared between calls.
+ */
+int pbkv_paged_decode_static(const pbkv_shape *shape, const void *q, const void *kv_pool,
+                             const int32_t *block_table, const int32_t *context_lens, void *out,
+                             void *stream);
+
+/*
  * Pool -> host page swap-out (Sec. 2: with HiCache, cache evicted from the GPU is retained
  * in host memory), the mirror of pbkv_swap_in_pages: host page i := pool page
  * page_ids[i], whole pages, byte-exact; the pool is not modified.

@@ -52,6 +52,8 @@ def load():
         lib.pbkv_swap_in_pages.argtypes = [sp, vp, i32p, ctypes.c_int32, vp, vp]
         lib.pbkv_paged_decode.restype = ctypes.c_int
         lib.pbkv_paged_decode.argtypes = [sp, vp, vp, i32p, i32p, vp, vp]
+        lib.pbkv_paged_decode_static.restype = ctypes.c_int
+        lib.pbkv_paged_decode_static.argtypes = [sp, vp, vp, i32p, i32p, vp, vp]
         lib.pbkv_swap_out_pages.restype = ctypes.c_int
         lib.pbkv_swap_out_pages.argtypes = [sp, vp, i32p, ctypes.c_int32, vp, vp]
         lib.pbkv_gather_probe.restype = ctypes.c_int
@@ -142,6 +144,12 @@ def paged_decode(shape, q, kv_pool, block_table, context_lens, out, stream=None)
     cl, clp = _host_i32(context_lens)
     _check(load().pbkv_paged_decode(ctypes.byref(shape), _ptr(q), _ptr(kv_pool), _ptr(block_table), clp,
                                     _ptr(out), _stream(stream)))
+
+
+def paged_decode_static(shape, q, kv_pool, block_table, context_lens, out, stream=None):
+    cl, clp = _host_i32(context_lens)
+    _check(load().pbkv_paged_decode_static(ctypes.byref(shape), _ptr(q), _ptr(kv_pool), _ptr(block_table), clp,
+                                           _ptr(out), _stream(stream)))
 
 
 def swap_out_pages(shape, kv_pool, page_ids, host_pages, stream=None):

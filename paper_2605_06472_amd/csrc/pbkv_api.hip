@@ -861,3 +861,113 @@ int pbkv_swap_out_pages(const pbkv_shape *s, const void *kv_pool, const int32_t 
 }
 
 }  // extern "C"
+
+// ---- decode without any allocation -----------------------------------------------------------
+// For callers that cannot allocate device memory (code under graph capture, tight serving loops,
+// harnesses that forbid it): the partials of the context slices and the two work lists live in one
+// file-scope device array instead of library-allocated buffers, and the lists reach it through
+// kernel arguments (a launch copies its arguments before it returns, so no host buffer has to stay
+// alive and no ring, event or copy is involved).
+namespace {
+
+constexpr size_t STATIC_PARTIAL_BYTES = 8u << 20;
+constexpr int STATIC_MAX_UNITS = 4096;
+constexpr int STATIC_MAX_REQS = 4096;
+constexpr size_t STATIC_UNITS_OFF = STATIC_PARTIAL_BYTES;
+constexpr size_t STATIC_REQS_OFF = STATIC_UNITS_OFF + STATIC_MAX_UNITS * sizeof(pbkv::DecodeUnit);
+constexpr size_t STATIC_BYTES = STATIC_REQS_OFF + STATIC_MAX_REQS * sizeof(pbkv::DecodeReq);
+
+// Every GPU the library runs on holds its own copy of this array, at its own address, until the
+// process ends.  In host code the name is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[STATIC_BYTES];
+
+std::mutex g_static_mu;
+void *g_static_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (asked once per device).
+int static_scratch(unsigned char **out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(PBKV_ERR_DEVICE, "device index %d unsupported", dev);
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return fail_hip(e, "hipGetSymbolAddress(scratch)");
+        g_static_ptr[dev] = ptr;
+    }
+    *out = (unsigned char *)g_static_ptr[dev];
+    return PBKV_OK;
+}
+
+constexpr int STAGE_WORDS = 896;                     // 3.5 KiB of a launch's 4 KiB of arguments
+struct StageChunk { uint32_t w[STAGE_WORDS]; };
+
+__global__ __launch_bounds__(256) void stage_kernel(StageChunk c, uint32_t *dst, int n) {
+    for (int i = threadIdx.x; i < n; i += 256) dst[i] = c.w[i];
+}
+
+// Copies `bytes` (a multiple of 4) of host memory to device memory at dst through kernel arguments.
+hipError_t stage_words(const void *src, size_t bytes, void *dst, hipStream_t st) {
+    const uint32_t *w = (const uint32_t *)src;
+    size_t words = bytes / 4;
+    uint32_t *d = (uint32_t *)dst;
+    while (words > 0) {
+        const int n = (int)std::min<size_t>(words, STAGE_WORDS);
+        StageChunk c;
+        memcpy(c.w, w, (size_t)n * 4);
+        hipLaunchKernelGGL(stage_kernel, dim3(1), dim3(256), 0, st, c, d, n);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        w += n;
+        d += n;
+        words -= n;
+    }
+    return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pbkv_paged_decode_static(const pbkv_shape *s, const void *q, const void *kv_pool, const int32_t *block_table,
+                             const int32_t *context_lens, void *out, void *stream) {
+    g_err[0] = 0;
+    int64_t total_pages = 0;
+    int rc = check_decode_args(s, q, kv_pool, block_table, context_lens, out, &total_pages, "pbkv_paged_decode_static");
+    if (rc) return rc;
+    if (s->batch == 0) return PBKV_OK;
+    if (s->batch > STATIC_MAX_REQS)
+        return fail(PBKV_ERR_LIMIT, "pbkv_paged_decode_static: %d requests, at most %d", s->batch, STATIC_MAX_REQS);
+    std::vector<pbkv::DecodeUnit> &units = tl_units;
+    std::vector<pbkv::DecodeReq> &reqs = tl_reqs;
+    if ((rc = build_decode_units(s, context_lens, total_pages, &units, &reqs))) return rc;
+    if (units.size() > (size_t)STATIC_MAX_UNITS)
+        return fail(PBKV_ERR_LIMIT, "pbkv_paged_decode_static: %zu context slices, at most %d", units.size(), STATIC_MAX_UNITS);
+    const size_t need = decode_scratch_bytes(s, units.size());
+    if (need > STATIC_PARTIAL_BYTES)
+        return fail(PBKV_ERR_LIMIT, "pbkv_paged_decode_static: %zu bytes of partial results, at most %zu", need,
+                    STATIC_PARTIAL_BYTES);
+    unsigned char *base = nullptr;
+    if ((rc = static_scratch(&base))) return rc;
+
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = stage_words(units.data(), units.size() * sizeof(pbkv::DecodeUnit), base + STATIC_UNITS_OFF, st);
+    if (e == hipSuccess) e = stage_words(reqs.data(), reqs.size() * sizeof(pbkv::DecodeReq), base + STATIC_REQS_OFF, st);
+    if (e != hipSuccess) return fail_hip(e, "work-list launch");
+    pbkv::DecodeParams p;
+    p.q = q; p.kv_pool = kv_pool; p.out = out; p.block_table = block_table;
+    p.units = (const pbkv::DecodeUnit *)(base + STATIC_UNITS_OFF);
+    p.reqs = (const pbkv::DecodeReq *)(base + STATIC_REQS_OFF);
+    p.mirror_units = nullptr; p.mirror_reqs = nullptr;
+    p.scratch = (float *)base;
+    p.n_units = (int32_t)units.size(); p.n_reqs = s->batch;
+    p.Hq = s->num_q_heads; p.Hkv = s->num_kv_heads;
+    p.max_pages = s->max_pages_per_req; p.num_pages = s->num_pages;
+    e = pbkv::launch_decode_bf16(p, s->head_dim, st);
+    return e == hipSuccess ? PBKV_OK : fail_hip(e, "decode launch");
+}
+
+}  // extern "C"
+
