@@ -98,8 +98,11 @@ int64_t pbkv_policy_bandwidth_budget_pages(const pbkv_policy *p, int64_t page_by
 /* Prefetch decision (Sec. 4.3): budget S = min(free_pages + retired pages, bw_budget_pages);
  * nothing unless the batch is pure decode.  Host nodes are taken in descending Value and
  * become GPU-tier; if they need more than free_pages, retired nodes are reclaimed (as in
- * eviction, honouring to_host) and listed in out_reclaimed.  Returns the number of nodes to
- * load (written to out_loads, at most load_capacity), *n_reclaimed the number reclaimed. */
+ * eviction, honouring to_host) and listed in out_reclaimed.  If the retired space cannot be
+ * reclaimed after all (out_reclaimed is full, or a retired node is held by a pinned or
+ * GPU-resident child), loads are withdrawn from the end of the list until the rest fits: the
+ * books always match the lists returned.  Returns the number of nodes to load (written to
+ * out_loads, at most load_capacity), *n_reclaimed the number reclaimed. */
 int64_t pbkv_policy_prefetch(pbkv_policy *p, int64_t free_pages, int64_t bw_budget_pages,
                              int32_t pure_decode, int32_t to_host, int64_t *out_loads,
                              int64_t load_capacity, int64_t *out_reclaimed,

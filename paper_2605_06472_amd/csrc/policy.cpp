@@ -466,17 +466,22 @@ int64_t pbkv_policy_prefetch(pbkv_policy *p, int64_t free_pages, int64_t bw_budg
         out_loads[n_loads++] = n->id;
     }
     int64_t freed = 0, n_rec = 0;
-    int rc = PBKV_OK;
     while (used - freed > free_pages) {
-        if (p->evictable.empty() || !p->retired(p->evictable.top()) || n_rec >= reclaim_capacity) {
-            rc = set_error(PBKV_ERR_LIMIT, "prefetch: retired space of %lld pages could not be reclaimed (list full or pinned)",
-                           (long long)(used - freed - free_pages));
-            break;
-        }
+        if (p->evictable.empty() || !p->retired(p->evictable.top()) || n_rec >= reclaim_capacity) break;
         Node *n = p->evictable.top();
         out_reclaimed[n_rec++] = n->id;
         freed += n->pages;
         p->leave_gpu(n, to_host != 0);
+    }
+    // Retired space that could not be reclaimed after all (the caller's list is full, or what is left
+    // of it is held by a pinned or GPU-resident child): the decision is cut back instead of being
+    // left half applied -- loads are withdrawn from the end (children before their parents) until
+    // the rest fits, so the books always describe what the caller is told to do.
+    while (used - freed > free_pages && n_loads > 0) {
+        Node *n = p->find(out_loads[--n_loads]);
+        n->pins--;
+        used -= n->pages;
+        p->set_tier(n, PBKV_TIER_HOST);
     }
     for (int64_t i = 0; i < n_loads; i++) {
         Node *n = p->find(out_loads[i]);
@@ -484,7 +489,7 @@ int64_t pbkv_policy_prefetch(pbkv_policy *p, int64_t free_pages, int64_t bw_budg
         p->refresh(n);
     }
     *n_reclaimed = n_rec;
-    return rc == PBKV_OK ? n_loads : rc;
+    return n_loads;
 }
 
 }  // extern "C"

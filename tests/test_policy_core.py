@@ -217,3 +217,34 @@ def test_policy_variants_rank_as_in_the_paper():
             tot += r["gpu_hit_pages"] + r["host_hit_pages"]
         rates.append(tot_hit / tot)
     assert rates[0] < rates[1] < rates[2] < rates[3], rates
+
+
+def test_prefetch_is_cut_back_when_the_reclaim_list_is_too_short():
+    """Two host nodes worth loading, no free page, retired GPU nodes that would make room -- but the
+    caller's reclaim list holds only one entry: the core withdraws the loads it cannot place instead
+    of leaving its books ahead of the lists it returns."""
+    pol = PC.Policy(3, 2, 0.7, PC.MODE_HE)
+    pol._b = pol._b[:1]                                # reclaim list of one node
+    pol.node_add(0, -1, 1, PC.GPU)                # root, accessed by both workflows
+    pol.node_add(1, 0, 2, PC.GPU)                 # will be retired
+    pol.node_add(2, 0, 2, PC.GPU)                 # will be retired
+    pol.node_add(3, 0, 2, PC.HOST)                # wanted
+    pol.node_add(4, 0, 2, PC.HOST)                # wanted
+    pol.access(7, 0, [0, 1])
+    pol.access(8, 0, [0, 2])
+    pol.terminate(7)
+    pol.terminate(8)
+    pol.access(9, 1, [0, 3])
+    pol.access(9, 2, [0, 4])
+    pol.forecast(9, [[0.0, 0.6, 0.4, 0.0], [0.0, 0.5, 0.5, 0.0]])
+    assert pol.retired_pages() == 4
+    loads, reclaimed = pol.prefetch(0, 100)
+    assert len(reclaimed) == 1 and len(loads) == 1
+    assert loads == [3]                                # the more valuable one stays
+    assert pol.node_tier(3) == PC.GPU and pol.node_tier(4) == PC.HOST
+    assert pol.node_tier(reclaimed[0]) == PC.HOST
+    assert pol.retired_pages() == 2
+    # the withdrawn node is still on offer next time
+    pol._b = np.zeros(8, np.int64)
+    loads, reclaimed = pol.prefetch(0, 100)
+    assert loads == [4] and len(reclaimed) == 1
