@@ -102,11 +102,12 @@ static __device__ __forceinline__ void static_for(F &&f, std::integer_sequence<i
 
 // Waves per work-group: 8 (one work-group per CU, its two waves per SIMD share one set of K/V
 // tiles) or 4 (two work-groups per CU, each staging its own tiles).  Eight waves stage every tile
-// once and win when work-groups are long; four overlap one work-group's prologue and epilogue
-// (three dependent fetches before the first tile step, the output stores after the last) with the
-// other's arithmetic and cut the work twice as fine, which wins when work-groups are short or few:
-// measured +3 % / +5 % / 0 / -5 % on launches whose 64-token blocks average 37 / 70 / 152 / 513
-// tile steps.  attn_bf16_force_waves(4|8) overrides the choice for the whole process (0: automatic).
+// once; four overlap one work-group's prologue and epilogue (dependent fetches before the first
+// tile step, the output stores after the last) with the other's arithmetic, cut the work twice as
+// fine and let the two waves of a SIMD drift apart instead of meeting at every barrier.  Measured
+// under sustained load (4 against 8 waves): +0.5 % / +3 % / +3.5 % / -3 % .. 0 on launches whose
+// 64-token blocks average 37 / 70 / 152 / 545 tile steps; the switch is at 256.
+// attn_bf16_force_waves(4|8) overrides the choice for the whole process (0: automatic).
 static std::atomic<int> g_forced_waves{0};
 void attn_bf16_force_waves(int waves) { g_forced_waves.store(waves == 4 || waves == 8 ? waves : 0); }
 int attn_bf16_forced_waves() { return g_forced_waves.load(); }
@@ -122,7 +123,7 @@ int attn_bf16_waves(const int32_t *prefix_lens, const int32_t *new_lens, int bat
             blocks++;
         }
     }
-    return blocks > 0 && steps < 128 * blocks ? 4 : 8;
+    return blocks > 0 && steps < 256 * blocks ? 4 : 8;
 }
 
 int attn_bf16_tile_tokens(int /*head_dim*/, int group, int waves) {

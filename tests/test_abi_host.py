@@ -171,7 +171,7 @@ def test_bench_refuses_more_than_one_gpu():
 
 def test_work_group_shape_follows_the_batch():
     """The bf16 attention kernel runs as four waves (32-token units) when the batch's 64-token blocks
-    average fewer than 128 tile steps, else as eight (64-token units); the size query of the gather
+    average fewer than 256 tile steps, else as eight (64-token units); the size query of the gather
     diagnostic reports the unit the attention call will use, without touching a device."""
     binding.set_attn_waves(0)
 
@@ -184,9 +184,9 @@ def test_work_group_shape_follows_the_batch():
     assert tok == 32 and n == 4 * 16 * 8
     n, tok = units(4, 32768, 2048, 2200)              # long histories: > 500 steps per block
     assert tok == 64 and n == 4 * 32 * 8
-    n, tok = units(2, 8000, 64, 520)                  # 127 steps: just below the switch
+    n, tok = units(2, 16192, 64, 1030)                # 255 steps: just below the switch
     assert tok == 32
-    n, tok = units(2, 8064, 64, 520)                  # 128 steps
+    n, tok = units(2, 16256, 64, 1030)                # 256 steps
     assert tok == 64
     try:
         binding.set_attn_waves(8)
