@@ -165,6 +165,32 @@ def test_rows_of_other_calls_are_untouched(oracle):
     assert_close(W.to_f64(to_numpy(big[4:4 + b.N])), _oracle(oracle, b), "bf16", "offset out")
 
 
+def test_more_streams_than_the_library_caches_for(oracle):
+    """The library keeps work lists for eight streams per device; calls rotating over twelve make it
+    hand the least recently used stream's slots to a new stream (after draining the device).  Every
+    call must still give the oracle's result, attention, append and decode alike."""
+    a = W.ragged_small(63, "bf16", prefix_lens=(300, 77, 0), new_lens=(130, 65, 70), num_pages=128)
+    dec = W.ragged_small(64, "bf16", Hq=8, Hkv=2, prefix_lens=(700, 33, 130), new_lens=(1, 1, 1), num_pages=128)
+    want = _oracle(oracle, a)
+    want_dec = oracle.decode(dec.q, dec.kv_pool, dec.block_table, dec.prefix_lens)
+    want_pool = oracle.append_kv(a.k_new, a.v_new, a.kv_pool, a.block_table, a.prefix_lens, a.new_lens)
+    streams = [torch.cuda.Stream() for _ in range(12)]
+    torch.cuda.synchronize()
+    for rnd in range(2):
+        for st in streams:
+            da, dd = DeviceBatch(a), DeviceBatch(dec)
+            out_dec = torch.full_like(dd.q, 7.0)
+            torch.cuda.synchronize()
+            da.prefill(stream=st)
+            da.append(stream=st)
+            binding.paged_decode(dd.shape, dd.q, dd.kv_pool, dd.block_table, dec.prefix_lens, out_dec, st)
+            da.prefill(stream=st)                      # the cached list of this stream
+            st.synchronize()
+            assert_close(da.out_f64(), want, "bf16", "stream rotation")
+            assert np.array_equal(to_numpy(da.kv_pool), want_pool)
+            assert_close(W.to_f64(to_numpy(out_dec)), want_dec, "bf16", "decode, stream rotation")
+
+
 # ------------------------------------------------------------------ invariants on the GPU
 def test_page_permutation_is_bit_identical_on_gpu():
     a = W.ragged_small(43, "bf16", prefix_lens=(300, 77, 1000, 0), new_lens=(200, 65, 130, 257),
