@@ -98,15 +98,17 @@ def sample_rows(b: W.Batch, per_request=6, unit=64, seed=0, max_boundaries=24):
 
 
 TOL = {"bf16": (2e-2, 1e-2), "f32": (1e-5, 1e-5)}    # (max abs error, relative L2 error)
-# The stress runs with Q scaled x8 (peaked softmax, outputs of order 1) get twice the absolute
-# bound.  The kernel folds log2(e)/sqrt(d) into Q and rounds the product once to bf16; that moves a
+# The stress runs with Q scaled x8 (peaked softmax, outputs of order 1) get one and a half times the
+# absolute bound.  The kernel folds log2(e)/sqrt(d) into Q and rounds the product once to bf16; that moves a
 # score by sigma = 2^-9/sqrt(3) * |c q * k|_2, about 0.0065 log2 units at x8 (0.0008 at x1), and in a
 # softmax that two keys dominate an output moves by up to ln2 * |delta_1 - delta_2| * 1/4 * |v_1 - v_2|,
 # about 0.03 for a 5-sigma pair and |v_1 - v_2| = 4.  A CPU emulation of the kernel's roundings on
 # 96 rows of the long-history batch gives 1.2e-2 with that rounding and 6e-3 without it (then the
 # final rounding of outputs near 3 is what is left); over the 3.5 million elements the test compares
-# the tail reaches 2.0e-2.  The relative L2 bound is the same as for the plain runs.
-PEAKED_ATOL = 4e-2
+# the tail reaches 2.0e-2 - 2.2e-2.  (A build that keeps Q exact and multiplies every score by the
+# scale instead passes these runs at 7e-3 and is 2.2 % slower on every configuration; the kernel
+# keeps the folded scale.)  The relative L2 bound is the same as for the plain runs.
+PEAKED_ATOL = 3e-2
 
 
 def assert_close(got, want, dtype, what="", atol=None):
