@@ -37,7 +37,10 @@
 //   * the scale log2(e)/sqrt(D) is folded into Q once, and the score MFMA chain starts
 //     from -M (M = running reference maximum, log2 units) instead of 0: the accumulator
 //     holds t = s - M directly and the softmax costs one exp2 per score, plus half a
-//     bf16 pack, half a dot2 (row sum of the ROUNDED probabilities) and half a max3;
+//     bf16 pack and half a dot2 (row sum of the ROUNDED probabilities).  The dot2 runs in
+//     the matrix pipe's order: one placed between two MFMAs holds the second one back
+//     until it has gone through, so the eight of a block are issued together, after the
+//     block's last MFMA, where they cost one such gap instead of eight;
 //   * that arithmetic is dealt out evenly over ALL MFMAs by working on 32-key blocks with
 //     the PV product two blocks behind the score product.  Iteration b:
 //         first half   t(b+1) = K(b+1) Q^T - M   on the MFMA  ||  exp2 of half of t(b)
@@ -499,7 +502,6 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
                 const bf16x2 pk = __builtin_convertvector(pv, bf16x2);
                 Pc[r / 8][r % 8] = pk[0];
                 Pc[r / 8][r % 8 + 1] = pk[1];
-                lb = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lb, false);   // sum of what PV will use
             };
             __builtin_amdgcn_sched_barrier(0);
 
@@ -549,14 +551,24 @@ void attn_bf16_kernel(AttnParams p, int G, int Gw) {
                 MFMA_PRIO(0);
                 if constexpr (H == 8) { if constexpr (s2 % 2 == 0) exp_pair(8 + s2); }
                 else exp_pair(8 + 2 * s2);
-                // the overflow probe of this block is evaluated here, beside the last MFMA, so that the
-                // next iteration starts with a branch on a scalar that is already there
-                if constexpr (s2 == H - 1) redo = __any(!(lb <= RESCALE_SUM));
+                // the row sum of the block (of what PV will use: the rounded probabilities), all eight
+                // dot2 in one run behind the last MFMA, and the overflow probe on it, so that the next
+                // iteration starts with a branch on a scalar that is already there
+                if constexpr (s2 == H - 1) {
+#pragma unroll
+                    for (int r = 0; r < 16; r += 2) {
+                        bf16x2 pk;
+                        pk[0] = Pc[r / 8][r % 8];
+                        pk[1] = Pc[r / 8][r % 8 + 1];
+                        lb = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lb, false);
+                    }
+                    redo = __any(!(lb <= RESCALE_SUM));
+                }
             }, std::make_integer_sequence<int, H>{});
             static_for([&](auto sc) {
                 constexpr int s2 = decltype(sc)::value, m = m0 + H + s2;
                 __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 1);
-                __builtin_amdgcn_sched_group_barrier(SG_VALU, 16 / H + (s2 == H - 1 ? 1 : 0), 1);
+                __builtin_amdgcn_sched_group_barrier(SG_VALU, s2 == H - 1 ? 12 : 16 / H, 1);
                 if constexpr (m + PF < NM) __builtin_amdgcn_sched_group_barrier(SG_DSRD, ((m + PF) / H) & 1 ? 2 : 1, 1);
             }, std::make_integer_sequence<int, H>{});
             PIN_V(Pc[1]);
