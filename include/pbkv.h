@@ -214,9 +214,10 @@ int pbkv_gather_probe(const pbkv_shape *shape, const void *k_new, const void *v_
 /*
  * Work-group shape of the bf16 attention kernel, for tests and tuning: 4 or 8 makes every later
  * pbkv_prefix_prefill / pbkv_gather_probe launch of this process use work-groups of that many
- * waves (32 or 64 suffix tokens per unit at a query/KV head ratio of 4), 0 returns to the
- * library's own choice per launch.  Results do not depend on it bit for bit.  Any other value:
- * PBKV_ERR_SHAPE.
+ * waves of 32 query rows (32 or 64 suffix tokens per unit at a query/KV head ratio of 4), 64 the
+ * form with four waves of 64 query rows (64 suffix tokens per unit at that ratio; the gather probe
+ * then runs as for 8, which stages the same tiles), 0 returns to the library's own choice per
+ * launch (4 or 64).  Results do not depend on it bit for bit.  Any other value: PBKV_ERR_SHAPE.
  */
 int pbkv_set_attn_waves(int waves);
 

@@ -114,7 +114,7 @@ def version():
 
 
 def set_attn_waves(waves):
-    """4 or 8: work-group shape of every later bf16 attention launch; 0: the library chooses."""
+    """4, 8 or 64: work-group shape of every later bf16 attention launch; 0: the library chooses."""
     _check(load().pbkv_set_attn_waves(int(waves)))
 
 

@@ -432,7 +432,7 @@ int64_t pbkv_page_bytes(const pbkv_shape *s) {
 
 int pbkv_set_attn_waves(int waves) {
     g_err[0] = 0;
-    if (waves != 0 && waves != 4 && waves != 8) return fail(PBKV_ERR_SHAPE, "pbkv_set_attn_waves: %d (0, 4 or 8)", waves);
+    if (waves != 0 && waves != 4 && waves != 8 && waves != 64) return fail(PBKV_ERR_SHAPE, "pbkv_set_attn_waves: %d (0, 4, 8 or 64)", waves);
     pbkv::attn_bf16_force_waves(waves);
     return PBKV_OK;
 }

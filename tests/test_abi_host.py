@@ -170,9 +170,9 @@ def test_bench_refuses_more_than_one_gpu():
 
 
 def test_work_group_shape_follows_the_batch():
-    """The bf16 attention kernel runs as four waves (32-token units) when the batch's 64-token blocks
-    average fewer than 256 tile steps, else as eight (64-token units); the size query of the gather
-    diagnostic reports the unit the attention call will use, without touching a device."""
+    """The bf16 attention kernel runs as four waves of 32 rows (32-token units) when the batch's 64-token
+    blocks average fewer than 100 tile steps, else as four waves of 64 rows (64-token units); the size
+    query of the gather diagnostic reports the unit the attention call will use, without touching a device."""
     binding.set_attn_waves(0)
 
     def units(batch, prefix, new, max_pages):
@@ -184,15 +184,17 @@ def test_work_group_shape_follows_the_batch():
     assert tok == 32 and n == 4 * 16 * 8
     n, tok = units(4, 32768, 2048, 2200)              # long histories: > 500 steps per block
     assert tok == 64 and n == 4 * 32 * 8
-    n, tok = units(2, 16192, 64, 1030)                # 255 steps: just below the switch
+    n, tok = units(2, 6208, 64, 400)                  # 99 steps: just below the switch
     assert tok == 32
-    n, tok = units(2, 16256, 64, 1030)                # 256 steps
+    n, tok = units(2, 6272, 64, 400)                  # 100 steps
     assert tok == 64
     try:
         binding.set_attn_waves(8)
         assert units(4, 2048, 512, 160)[1] == 64
         binding.set_attn_waves(4)
         assert units(4, 32768, 2048, 2200)[1] == 32
+        binding.set_attn_waves(64)
+        assert units(4, 2048, 512, 160)[1] == 64
         with pytest.raises(binding.PbkvError) as e:
             binding.set_attn_waves(6)
         assert e.value.code == -2

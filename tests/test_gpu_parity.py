@@ -78,11 +78,11 @@ def force_waves():
     binding.set_attn_waves(0)
 
 
-@pytest.mark.parametrize("waves", [4, 8])
+@pytest.mark.parametrize("waves", [4, 8, 64])
 @pytest.mark.parametrize("name", sorted(n for n in RAGGED if n.startswith("bf16")))
-def test_both_work_group_shapes_of_the_bf16_kernel(oracle, name, waves, force_waves):
-    """The library picks the work-group shape (4 or 8 waves) from the batch; small batches like these
-    would only ever see one of them, so both are forced in turn."""
+def test_every_work_group_shape_of_the_bf16_kernel(oracle, name, waves, force_waves):
+    """The library picks the work-group shape (4 waves of 32 rows or 4 of 64; 8 of 32 on request) from
+    the batch; small batches like these would only ever see one of them, so each is forced in turn."""
     force_waves(waves)
     b = W.ragged_small(40, **RAGGED[name])
     _check_full(oracle, b, "%s, %s waves" % (name, waves))
@@ -92,13 +92,14 @@ def test_the_work_group_shape_does_not_change_a_bit(force_waves):
     """A row is computed by one wave in the same order of operations whichever shape the launch has."""
     b = W.ragged_small(41, "bf16", prefix_lens=(300, 77, 1000, 0), new_lens=(200, 65, 130, 257), num_pages=256, q_scale=8.0)
     outs = []
-    for waves in (4, 8):
+    for waves in (4, 8, 64):
         force_waves(waves)
         db = DeviceBatch(b)
         db.prefill()
         torch.cuda.synchronize()
         outs.append(to_numpy(db.out))
     assert np.array_equal(outs[0], outs[1])
+    assert np.array_equal(outs[0], outs[2])
 
 
 def test_repeated_calls_launch_from_the_cached_work_list(oracle):
@@ -311,8 +312,8 @@ def test_cfg2_dynamic_workflow(oracle, q_scale):
     _check_sampled(oracle, b, "cfg2 q_scale=%g" % q_scale, atol=PEAKED_ATOL if q_scale > 1 else None)
 
 
-@pytest.mark.parametrize("waves", [4, 8])
-def test_cfg2_peaked_in_both_work_group_shapes(oracle, waves, force_waves):
+@pytest.mark.parametrize("waves", [4, 8, 64])
+def test_cfg2_peaked_in_every_work_group_shape(oracle, waves, force_waves):
     force_waves(waves)
     b = W.dynamic_workflow_batch(q_scale=8.0)
     _check_sampled(oracle, b, "cfg2 q_scale=8, %d waves" % waves, atol=PEAKED_ATOL)
