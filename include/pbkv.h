@@ -64,7 +64,7 @@ typedef enum {
     PBKV_ERR_ALIAS = -5,   /* duplicate destination pages in a swap-in            */
     PBKV_ERR_DEVICE = -6,  /* HIP runtime error, or a pointer of the wrong kind   */
     PBKV_ERR_LIMIT = -7    /* the call needs more descriptor space than the library
-                              can provide at once                                 */
+                              can provide at once, or the pool is 1 TiB or more   */
 } pbkv_status;
 
 typedef enum { PBKV_BF16 = 0, PBKV_F32 = 1 } pbkv_dtype;

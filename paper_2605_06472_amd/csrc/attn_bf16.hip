@@ -766,20 +766,27 @@ void attn_bf16_w64_kernel(AttnParams p, int G, int Gw) {
     const int slot0 = (w * Gm::RW) & 15;
     const int32_t *bt = p.block_table + (int64_t)td.req * p.max_pages;
     const int n_prefix_pages = (td.prefix_len + 15) >> 4;
+    // A wave alone on its SIMD pays for every scalar instruction, so the page ids are held as page
+    // offsets in units of 256 bytes (a page is a multiple of that, and a pool of less than 1 TiB
+    // keeps them in 32 bits; the host checks it): a tile's K address is one lane read, one shift and
+    // one 64-bit add.
+    const int row_pitch = p.Hkv * ROWB;
+    const int64_t page_bytes = 2 * (int64_t)p.Hkv * 16 * ROWB;
+    const unsigned page_units = (unsigned)(page_bytes >> 8);
     auto load_id_block = [&](int blk) {
         const int lp = blk * 64 + l;
         int pg = lp < n_prefix_pages ? bt[lp] : 0;
         pg = pg < 0 ? 0 : (pg >= p.num_pages ? p.num_pages - 1 : pg);
-        return pg;
+        return (int)((unsigned)pg * page_units);
     };
     int ids_cur = load_id_block(0), ids_next = load_id_block(1);
     struct Src { const char *k, *v; int nrec; };
-    const int row_pitch = p.Hkv * ROWB;
-    const int64_t page_bytes = 2 * (int64_t)p.Hkv * 16 * ROWB;
     const int64_t v_in_page = (int64_t)p.Hkv * 16 * ROWB;
     const char *pool_k = (const char *)p.kv_pool + (int64_t)kvh * 16 * ROWB;
     const char *kn_h = (const char *)p.k_new + (int64_t)kvh * ROWB;
     const char *vn_h = (const char *)p.v_new + (int64_t)kvh * ROWB;
+    // rows of this wave's page of the last prefix tile (the only one that can be partly filled or unused)
+    const int last_nrec = min(max(td.prefix_len - ((TP - 1) * PPT + pw) * 16, 0), 16) * ROWB;
     auto tile_src = [&](int t) {
         Src s;
         if (t < TP) {
@@ -787,11 +794,10 @@ void attn_bf16_w64_kernel(AttnParams p, int G, int Gw) {
                 ids_cur = ids_next;
                 ids_next = load_id_block((t >> 4) + 1);
             }
-            const int pg = __builtin_amdgcn_readlane(ids_cur, (t & 15) * PPT + pw);
-            const int rows = t < TP - 1 ? 16 : max(td.prefix_len - (t * PPT + pw) * 16, 0);
-            s.k = pool_k + pg * page_bytes;
+            const unsigned units = (unsigned)__builtin_amdgcn_readlane(ids_cur, (t & 15) * PPT + pw);
+            s.k = pool_k + ((uint64_t)units << 8);
             s.v = s.k + v_in_page;
-            s.nrec = rows * ROWB;
+            s.nrec = t < TP - 1 ? 16 * ROWB : last_nrec;
         } else {
             const int s0 = (t - TP) * BN + w * Gm::RW;
             const int srows = min(tok_end - s0, Gm::RW);

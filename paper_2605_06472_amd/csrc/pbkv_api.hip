@@ -56,6 +56,9 @@ int check_shape(const pbkv_shape *s, bool need_heads) {
         return fail(PBKV_ERR_SHAPE, "head_dim %d unsupported (64, 128)", s->head_dim);
     if (s->num_kv_heads <= 0) return fail(PBKV_ERR_SHAPE, "num_kv_heads %d", s->num_kv_heads);
     if (s->num_pages <= 0) return fail(PBKV_ERR_SHAPE, "num_pages %d", s->num_pages);
+    // the attention kernel addresses pool pages by 32-bit offsets in units of 256 bytes
+    if ((int64_t)s->num_pages * 2 * s->num_kv_heads * s->page_size * s->head_dim * elt_bytes(s->dtype) >= ((int64_t)1 << 40))
+        return fail(PBKV_ERR_LIMIT, "pool of %d pages is 1 TiB or more", s->num_pages);
     if (need_heads) {
         if (s->num_q_heads <= 0 || s->num_q_heads % s->num_kv_heads != 0)
             return fail(PBKV_ERR_SHAPE, "num_q_heads %d is not a multiple of num_kv_heads %d",
