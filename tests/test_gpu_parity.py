@@ -88,6 +88,26 @@ def test_every_work_group_shape_of_the_bf16_kernel(oracle, name, waves, force_wa
     _check_full(oracle, b, "%s, %s waves" % (name, waves))
 
 
+MID = {
+    "d64_g4": dict(Hq=8, Hkv=2, d=64),
+    "d128_g8": dict(Hq=16, Hkv=2, d=128),
+    "d128_g1": dict(Hq=2, Hkv=2, d=128),
+    "d64_g16": dict(Hq=16, Hkv=1, d=64),
+}
+
+
+@pytest.mark.parametrize("waves", [4, 8, 64])
+@pytest.mark.parametrize("name", sorted(MID))
+def test_prefixes_of_several_page_id_blocks_in_every_shape(oracle, name, waves, force_waves):
+    """The kernels hold 64 page ids (16 tiles) at a time and load the next block while the current one
+    is in use; prefixes of 35 to 52 tiles take every work-group shape through two or three such
+    reloads, a partly filled last page and a ragged suffix, for the head shapes the full-size
+    configurations do not have."""
+    force_waves(waves)
+    b = W.ragged_small(43, "bf16", prefix_lens=(3301, 2240, 0, 2900), new_lens=(150, 65, 130, 1), num_pages=640, **MID[name])
+    _check_sampled(oracle, b, "%s, %d waves" % (name, waves), per_request=24, max_boundaries=8)
+
+
 def test_the_work_group_shape_does_not_change_a_bit(force_waves):
     """A row is computed by one wave in the same order of operations whichever shape the launch has."""
     b = W.ragged_small(41, "bf16", prefix_lens=(300, 77, 1000, 0), new_lens=(200, 65, 130, 257), num_pages=256, q_scale=8.0)
