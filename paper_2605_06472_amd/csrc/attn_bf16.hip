@@ -921,8 +921,10 @@ void attn_bf16_w64_kernel(AttnParams p, int G, int Gw) {
         Pc[r / 8][r % 8 + 1] = pk[1];
         lbs = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lbs, false);
     };
-    // the same in two halves, so that the wave's one instruction stream can put an MFMA between the
-    // exponentials and the instructions that depend on them
+    // The common path's form of it, in two halves, so that the wave's one instruction stream has an MFMA
+    // between the exponentials and the pack that depends on them; assembly statements, because they
+    // must stay where they are written (plain intrinsics carry no ordering against the MFMA statements).
+    // The row sums are not formed here: see block_sums.
     auto exp_pair_a = [&](const f32x16 &Tc, int r) __attribute__((always_inline)) {
         f32x2 pv;
         float a, b;
@@ -932,14 +934,17 @@ void attn_bf16_w64_kernel(AttnParams p, int G, int Gw) {
         pv[1] = b;
         return pv;
     };
-    auto exp_pair_b = [&](const f32x2 &pv, bf16x8 (&Pc)[2], float &lbs, int r) __attribute__((always_inline)) {
+    auto exp_pair_b = [&](const f32x2 &pv, bf16x8 (&Pc)[2], int r) __attribute__((always_inline)) {
         int bits;
         asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(bits) : "v"(pv[0]), "v"(pv[1]));
         i32x4 t = __builtin_bit_cast(i32x4, Pc[r / 8]);
         t[(r % 8) / 2] = bits;
         Pc[r / 8] = __builtin_bit_cast(bf16x8, t);
-        (void)lbs;
     };
+    // Row sums of a finished block of both sub-tiles, from its packed (rounded) probabilities, in
+    // score order: the same dot2 chain as the other forms of the kernel run.  A dot2 goes through the
+    // matrix pipe in order with the MFMAs, so the sixteen stand together, at the start of the
+    // iteration that multiplies the block with V, where the overflow test needs them.
     auto block_sums = [&](const bf16x8 (&Pp)[2][2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < 2; s++) {
@@ -1039,7 +1044,7 @@ void attn_bf16_w64_kernel(AttnParams p, int G, int Gw) {
             lb[1] = 0.f;
             __builtin_amdgcn_sched_barrier(0);
             // first half: t(b+1) = K Q^T - M for both sub-tiles  ||  probabilities of sub-tile 0's block b; tile loads.
-            // Order inside a group: MFMA, exponentials, MFMA, pack and row sum -- a wave issues in order, so two
+            // Order inside a group: MFMA, exponentials, MFMA, tile load, pack -- a wave issues in order, so two
             // MFMAs back to back would hold the vector work behind the second one's wait for the matrix pipe
             static_for([&](auto sc) {
                 constexpr int s2 = decltype(sc)::value, m = m0 + s2;
@@ -1058,7 +1063,7 @@ void attn_bf16_w64_kernel(AttnParams p, int G, int Gw) {
                     if constexpr (s2 % 2 == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_k, dst_k, 16, ok.v[li2], 0, li2 * 1024, 0);
                     else __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_v, dst_v, 16, ov.v[li2], 0, li2 * 1024, 0);
                 }
-                static_for([&](auto pc) { exp_pair_b(pv[pc.value], Pc[0], lb[0], 2 * (PPG * s2 + pc.value)); }, std::make_integer_sequence<int, PPG>{});
+                static_for([&](auto pc) { exp_pair_b(pv[pc.value], Pc[0], 2 * (PPG * s2 + pc.value)); }, std::make_integer_sequence<int, PPG>{});
                 __builtin_amdgcn_sched_barrier(0);
             }, std::make_integer_sequence<int, H>{});
             if (__builtin_expect(masked, 0)) {
@@ -1082,7 +1087,7 @@ void attn_bf16_w64_kernel(AttnParams p, int G, int Gw) {
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_o_acc(O[1][s2 % Gm::DB], op[m % (PFW + 1)], as_i(Pp[1][s2 / Gm::DB]));
                 __builtin_amdgcn_sched_barrier(0);
-                static_for([&](auto pc) { exp_pair_b(pv[pc.value], Pc[1], lb[1], 2 * (PPG * s2 + pc.value)); }, std::make_integer_sequence<int, PPG>{});
+                static_for([&](auto pc) { exp_pair_b(pv[pc.value], Pc[1], 2 * (PPG * s2 + pc.value)); }, std::make_integer_sequence<int, PPG>{});
                 __builtin_amdgcn_sched_barrier(0);
             }, std::make_integer_sequence<int, H>{});
         };
