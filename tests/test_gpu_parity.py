@@ -355,15 +355,7 @@ def test_long_context_with_a_moving_reference(oracle, slope):
     threshold at which the kernel moves its reference, so the redo path runs at nearly every block
     of every step -- or fall at that rate (the reference stays where the first block put it and the
     later probabilities vanish)."""
-    b = W.long_history(seed=1013, batch=1, num_pages=4096)
-    d, p, n = b.d, int(b.prefix_lens[0]), int(b.new_lens[0])
-    u = np.sign(np.random.default_rng(3).standard_normal(d)).astype(np.float32)       # |u|^2 = d
-    b.q = W.f32_to_bf16_bits(np.broadcast_to(4.0 * u, (n, b.Hq, d)).astype(np.float32))
-    t = np.arange(p + n, dtype=np.float32) + 1.0
-    keys = W.f32_to_bf16_bits((slope * t)[:, None, None] * np.broadcast_to(u, (p + n, b.Hkv, d)))
-    pages = b.block_table[0, :p // b.P]
-    b.kv_pool[pages, 0] = keys[:p].reshape(p // b.P, b.P, b.Hkv, d).transpose(0, 2, 1, 3)
-    b.k_new[:] = keys[p:]
+    b = _moving_reference_batch(slope)
     db = DeviceBatch(b)
     unit = attention_unit(db)
     assert unit == 64
@@ -373,6 +365,41 @@ def test_long_context_with_a_moving_reference(oracle, slope):
     want = _oracle(oracle, b, rows=rows)
     err, rel = assert_close(db.out_f64()[rows], want, "bf16", "moving reference, slope %g" % slope)
     print("moving reference slope %g: rows %d max abs err %.3e rel L2 %.3e" % (slope, len(rows), err, rel), flush=True)
+
+
+def _moving_reference_batch(slope):
+    b = W.long_history(seed=1013, batch=1, num_pages=4096)
+    d, p, n = b.d, int(b.prefix_lens[0]), int(b.new_lens[0])
+    u = np.sign(np.random.default_rng(3).standard_normal(d)).astype(np.float32)
+    b.q = W.f32_to_bf16_bits(np.broadcast_to(4.0 * u, (n, b.Hq, d)).astype(np.float32))
+    t = np.arange(p + n, dtype=np.float32) + 1.0
+    keys = W.f32_to_bf16_bits((slope * t)[:, None, None] * np.broadcast_to(u, (p + n, b.Hkv, d)))
+    pages = b.block_table[0, :p // b.P]
+    b.kv_pool[pages, 0] = keys[:p].reshape(p // b.P, b.P, b.Hkv, d).transpose(0, 2, 1, 3)
+    b.k_new[:] = keys[p:]
+    return b
+
+
+@pytest.mark.parametrize("case", ["cfg4_peaked", "moving_reference"])
+def test_full_size_outputs_are_the_same_bits_in_every_shape(case, force_waves):
+    """The three work-group shapes run the same arithmetic per row in the same order, one of them
+    with its matrix and softmax instructions placed and its hazards kept by hand: at full size and
+    under full load their outputs must agree bit for bit -- on the mixed batch with peaked scores, and
+    on the batch whose reference moves at nearly every block."""
+    b = W.mixed_hit_miss(q_scale=8.0) if case == "cfg4_peaked" else _moving_reference_batch(0.0062)
+    db = DeviceBatch(b)
+    if b.host_pages is not None:
+        db.swap_in()
+    outs = []
+    for waves in (4, 8, 64):
+        force_waves(waves)
+        db.out.zero_()
+        db.prefill()
+        torch.cuda.synchronize()
+        outs.append(db.out.clone())
+    assert torch.isfinite(outs[0].float()).all()
+    assert torch.equal(outs[0], outs[1]), "4 against 8 waves"
+    assert torch.equal(outs[0], outs[2]), "4 waves against the 64-row form"
 
 
 @pytest.mark.parametrize("q_scale", [1.0, 8.0])
