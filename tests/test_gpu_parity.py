@@ -351,7 +351,7 @@ def test_cfg3_long_history(oracle, q_scale):
 @pytest.mark.parametrize("slope", [0.0062, -0.0062], ids=["rising", "falling"])
 def test_long_context_with_a_moving_reference(oracle, slope):
     """One request of the long-history size (32768 cached + 2048 new tokens, 545 tile steps in the
-    eight-wave shape) whose scores climb by about 13 log2 units per 32-key block -- past the
+    64-token units) whose scores climb by about 13 log2 units per 32-key block -- past the
     threshold at which the kernel moves its reference, so the redo path runs at nearly every block
     of every step -- or fall at that rate (the reference stays where the first block put it and the
     later probabilities vanish)."""
@@ -435,7 +435,7 @@ def test_cfg4_mixed_hit_miss_with_swap_in(oracle, q_scale):
     db.append(stream=side)
     torch.cuda.synchronize()
     resident = oracle.swap_in(b.host_pages, b.swap_page_ids, b.kv_pool)
-    # single-request calls take the 4- or 8-wave shape request by request: sample around both unit sizes
+    # single-request calls take the 32-row or the 64-row shape request by request: sample around both unit sizes
     rows = np.union1d(sample_rows(b, per_request=40, unit=64, max_boundaries=12),
                       sample_rows(b, per_request=0, unit=32, max_boundaries=12, seed=1))
     want = oracle.prefill(b.q, b.k_new, b.v_new, resident, b.block_table, b.prefix_lens, b.new_lens, rows=rows)
