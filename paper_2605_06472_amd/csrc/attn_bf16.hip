@@ -110,8 +110,9 @@ static __device__ __forceinline__ void static_for(F &&f, std::integer_sequence<i
 //       for short work units.
 //   8 waves, 32 rows each:  one work-group per CU, two waves per SIMD sharing one set of tiles.
 //   64 (four waves of 64 rows each, attn_bf16_w64_kernel below): one wave per SIMD; every LDS operand
-//       feeds two MFMAs and a tile is staged once per 256 rows, so a tile step moves half the LDS
-//       bytes and a quarter of the staged bytes per FLOP.  The chip is power-limited under this
+//       feeds two MFMAs and a tile is staged once per 256 rows, so a tile step reads half the LDS
+//       bytes per FLOP of either 32-row shape and stages as the 8-wave shape does (half of what
+//       the 4-wave shape stages).  The chip is power-limited under this
 //       kernel, so that is speed: measured against the better of the other two, under sustained
 //       load, -1 % / -1.5 % / +4.5 % / +3 % on launches whose 64-token blocks average 37 / 70 / 152 /
 //       545 tile steps.  The switch from 4 waves is at 100.
